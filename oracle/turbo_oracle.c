@@ -1,0 +1,158 @@
+/*
+ * CPU oracle for the two batch-reduction operations of the TurboTransformers
+ * paper (Section 4.1.2, "GPU-based Batch-Reduction").
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT PATH.  Only the test
+ * suite, the smoke check and the benchmark's CPU-baseline leg may call it.
+ * It shares no code, header, table or helper with the HIP library.
+ *
+ * Both operations are exact definitions that the paper's method reaches
+ * faster, so the oracle is the plain definition, one row at a time, in
+ * double precision:
+ *
+ *   - Softmax "calculates summation and maximum" on the low dimension of a
+ *     2-D view (Section 4.1.2); in attention it is applied to the scaled
+ *     query-key dot products (Section 2.1).  The additive mask is the
+ *     padding convention of Section 2.1 (short sequences are zero-padded to
+ *     the longest one in the batch).
+ *   - LayerNorm "calculates the mean and variance" (Section 4.1.2); the
+ *     variance is the population variance of Equation 1.  The fused kernel
+ *     ("AddBiasLayerNorm", Section 6.2.1) normalises x + bias + residual.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_pins.py
+ * (hand cases, closed forms, invariants, library special cases).  Nothing is
+ * "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int g_threads = 1;
+
+/* Number of host threads the row loops may use (rows are independent). */
+void oracle_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+int oracle_get_threads(void) { return g_threads; }
+
+/*
+ * Scaled, masked softmax over the last axis of scores[B][H][Sq][Sk].
+ *   z_k = scale * s_k + mask_k ;  m = max_k z_k ;  e_k = exp(z_k - m) ;
+ *   y_k = e_k / sum_k e_k.
+ * mask may be NULL.  Otherwise mask element (b, q, k) lives at
+ * mask[b*mask_stride_b + q*mask_stride_q + k] and is shared by all heads.
+ * Nothing is special-cased for masked entries: they become 0 only because
+ * exp() of a very negative number underflows.
+ */
+void oracle_masked_softmax(const double *scores, const double *mask, long long mask_stride_b,
+                           long long mask_stride_q, int B, int H, int Sq, int Sk, double scale, double *out)
+{
+    long long n_rows = (long long)B * H * Sq;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long long row = 0; row < n_rows; ++row) {
+        long long q = row % Sq;
+        long long b = row / ((long long)H * Sq);
+        const double *s = scores + row * Sk;
+        const double *a = mask ? mask + b * mask_stride_b + q * mask_stride_q : NULL;
+        double *y = out + row * Sk;
+
+        double m = -INFINITY;
+        for (int k = 0; k < Sk; ++k) {
+            double z = scale * s[k] + (a ? a[k] : 0.0);
+            y[k] = z;
+            if (z > m) m = z;
+        }
+        double l = 0.0;
+        for (int k = 0; k < Sk; ++k) {
+            y[k] = exp(y[k] - m);
+            l += y[k];
+        }
+        for (int k = 0; k < Sk; ++k) y[k] /= l;
+    }
+}
+
+/*
+ * out[r][j] = (t_j - mu) / sqrt(var + eps) * gamma_j + beta_j  with
+ * t_j = x[r][j] + bias_j + residual[r][j],  mu = mean_j t_j,
+ * var = mean_j (t_j - mu)^2   (population variance, first form of Eq. 1).
+ * bias and residual may be NULL (treated as zeros).
+ */
+void oracle_add_bias_layernorm(const double *x, const double *residual, const double *bias, const double *gamma,
+                               const double *beta, long long rows, int hidden, double eps, double *out)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long long r = 0; r < rows; ++r) {
+        const double *xr = x + r * hidden;
+        const double *rr = residual ? residual + r * hidden : NULL;
+        double *o = out + r * hidden;
+
+        double sum = 0.0;
+        for (int j = 0; j < hidden; ++j) {
+            double t = xr[j] + (bias ? bias[j] : 0.0) + (rr ? rr[j] : 0.0);
+            o[j] = t;
+            sum += t;
+        }
+        double mu = sum / hidden;
+        double ss = 0.0;
+        for (int j = 0; j < hidden; ++j) {
+            double d = o[j] - mu;
+            ss += d * d;
+        }
+        double var = ss / hidden;
+        double inv = 1.0 / sqrt(var + eps);
+        for (int j = 0; j < hidden; ++j) o[j] = (o[j] - mu) * inv * gamma[j] + beta[j];
+    }
+}
+
+/* ---- the three variance algorithms that Equation 1 relates ------------- */
+
+/* E(x - E x)^2: two reductions, the form the paper attributes to the baseline. */
+double oracle_variance_two_pass(const double *x, int n)
+{
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += x[i];
+    double mu = s / n, ss = 0.0;
+    for (int i = 0; i < n; ++i) ss += (x[i] - mu) * (x[i] - mu);
+    return ss / n;
+}
+
+/* E(x^2) - E^2(x): x and x^2 reduced together, the form the paper adopts. */
+double oracle_variance_sum_of_squares(const double *x, int n)
+{
+    double s = 0.0, s2 = 0.0;
+    for (int i = 0; i < n; ++i) {
+        s += x[i];
+        s2 += x[i] * x[i];
+    }
+    double mu = s / n;
+    return s2 / n - mu * mu;
+}
+
+/* Welford's running (count, mean, M2) update: one pass like the form above,
+ * without the cancellation it suffers when |mean| >> std. */
+double oracle_variance_welford(const double *x, int n)
+{
+    double mean = 0.0, m2 = 0.0;
+    for (int i = 0; i < n; ++i) {
+        double d = x[i] - mean;
+        mean += d / (i + 1);
+        m2 += d * (x[i] - mean);
+    }
+    return m2 / n;
+}
+
+/* Merge of two (count, mean, M2) states (Chan et al.), used by tests to check
+ * that splitting a row in any way gives the same statistics. */
+void oracle_welford_merge(double na, double mean_a, double m2_a, double nb, double mean_b, double m2_b,
+                          double *n, double *mean, double *m2)
+{
+    double nt = na + nb;
+    if (nt == 0.0) {
+        *n = 0.0; *mean = 0.0; *m2 = 0.0;
+        return;
+    }
+    double d = mean_b - mean_a;
+    *n = nt;
+    *mean = mean_a + d * (nb / nt);
+    *m2 = m2_a + m2_b + d * d * (na * nb / nt);
+}

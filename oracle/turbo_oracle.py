@@ -1,0 +1,136 @@
+"""ctypes front end of the double-precision CPU oracle (oracle/turbo_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module.
+
+Inputs of any float dtype are widened exactly to float64 before the call, so
+for fp16 I/O the oracle sees the fp16-rounded values and returns float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "turbo_oracle.c")
+_LIB = os.path.join(_HERE, "libturbo_oracle.so")
+_lib = None
+
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2, OpenMP for the row loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_set_threads.argtypes = [ctypes.c_int]
+        lib.oracle_get_threads.restype = ctypes.c_int
+        lib.oracle_masked_softmax.argtypes = [_dp, _dp, ctypes.c_longlong, ctypes.c_longlong, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, _dp]
+        lib.oracle_masked_softmax.restype = None
+        lib.oracle_add_bias_layernorm.argtypes = [_dp, _dp, _dp, _dp, _dp, ctypes.c_longlong, ctypes.c_int,
+                                                  ctypes.c_double, _dp]
+        lib.oracle_add_bias_layernorm.restype = None
+        for name in ("oracle_variance_two_pass", "oracle_variance_sum_of_squares", "oracle_variance_welford"):
+            f = getattr(lib, name)
+            f.argtypes = [_dp, ctypes.c_int]
+            f.restype = ctypes.c_double
+        lib.oracle_welford_merge.argtypes = [ctypes.c_double] * 6 + [_dp] * 3
+        lib.oracle_welford_merge.restype = None
+        _lib = lib
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_dp)
+
+
+def set_threads(n: int) -> None:
+    _load().oracle_set_threads(int(n))
+
+
+def get_threads() -> int:
+    return int(_load().oracle_get_threads())
+
+
+def masked_softmax(scores, mask=None, mask_stride_b: int = 0, mask_stride_q: int = 0, scale: float = 1.0) -> np.ndarray:
+    """softmax_k(scale * scores + mask) over the last axis of a [B,H,Sq,Sk] array; float64 result.
+
+    `mask` (any shape, flattened) is addressed as mask[b*mask_stride_b + q*mask_stride_q + k].
+    """
+    s = _f64(scores)
+    if s.ndim != 4:
+        raise ValueError("scores must be [B,H,Sq,Sk]")
+    B, H, Sq, Sk = s.shape
+    m = None
+    if mask is not None:
+        m = _f64(mask).reshape(-1)
+        need = (B - 1) * mask_stride_b + (Sq - 1) * mask_stride_q + Sk
+        if m.size < need:
+            raise ValueError("mask too small for the given strides")
+    out = np.empty_like(s)
+    if s.size:
+        _load().oracle_masked_softmax(_ptr(s), _ptr(m), int(mask_stride_b), int(mask_stride_q), B, H, Sq, Sk,
+                                      float(scale), _ptr(out))
+    return out
+
+
+def add_bias_layernorm(x, residual, bias, gamma, beta, eps: float) -> np.ndarray:
+    """LayerNorm(x + bias + residual) * gamma + beta over the last axis of [rows, hidden]; float64 result."""
+    xx = _f64(x)
+    if xx.ndim != 2:
+        raise ValueError("x must be [rows, hidden]")
+    rows, hidden = xx.shape
+    rr = None if residual is None else _f64(residual)
+    bb = None if bias is None else _f64(bias)
+    gg, be = _f64(gamma), _f64(beta)
+    if rr is not None and rr.shape != xx.shape:
+        raise ValueError("residual shape")
+    for v in (bb, gg, be):
+        if v is not None and v.shape != (hidden,):
+            raise ValueError("parameter vector shape")
+    out = np.empty_like(xx)
+    if xx.size:
+        _load().oracle_add_bias_layernorm(_ptr(xx), _ptr(rr), _ptr(bb), _ptr(gg), _ptr(be), rows, hidden,
+                                          float(eps), _ptr(out))
+    return out
+
+
+def variance_two_pass(x) -> float:
+    v = _f64(x).reshape(-1)
+    return float(_load().oracle_variance_two_pass(_ptr(v), v.size))
+
+
+def variance_sum_of_squares(x) -> float:
+    v = _f64(x).reshape(-1)
+    return float(_load().oracle_variance_sum_of_squares(_ptr(v), v.size))
+
+
+def variance_welford(x) -> float:
+    v = _f64(x).reshape(-1)
+    return float(_load().oracle_variance_welford(_ptr(v), v.size))
+
+
+def welford_merge(a, b):
+    """Merge two (count, mean, M2) triples."""
+    n, mean, m2 = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _load().oracle_welford_merge(*(float(v) for v in a), *(float(v) for v in b), ctypes.byref(n),
+                                 ctypes.byref(mean), ctypes.byref(m2))
+    return n.value, mean.value, m2.value
