@@ -1,0 +1,138 @@
+/*
+ * turbo_reduce.h - C ABI of the MI355X (gfx950) batch-reduction library.
+ *
+ * The two operations are the "batch reduction" kernels of the
+ * TurboTransformers paper, Section 4.1.2: on the low dimension of a 2-D view
+ * of a tensor, Softmax needs a maximum and a sum per row, LayerNorm a mean
+ * and a variance per row, for a whole batch of rows at once.
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device.  The
+ *     caller owns every buffer; the library allocates nothing, keeps no
+ *     workspace and never synchronises.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the null stream) and the call
+ *     returns immediately.
+ *   - Tensors are dense, row-major, last index fastest.
+ *   - The return value is a TURBO_* status.  Argument validation happens
+ *     before the first HIP call, so every error except TURBO_ERR_LAUNCH is
+ *     reported without touching the GPU and without enqueuing work.
+ *   - A size of zero (or below) in any dimension is TURBO_ERR_SHAPE: an empty
+ *     call is treated as a caller bug, not as a no-op.
+ *   - Base pointers must be aligned to the element size (TURBO_ERR_ALIGN
+ *     otherwise).  16-byte alignment together with a row length that is a
+ *     multiple of 16 bytes selects the widest loads; nothing more is required.
+ *   - Non-finite inputs are outside the contract.
+ */
+#ifndef TURBO_REDUCE_H
+#define TURBO_REDUCE_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum turbo_status {
+    TURBO_OK = 0,
+    TURBO_ERR_NULL = 1,   /* a required pointer is NULL */
+    TURBO_ERR_SHAPE = 2,  /* a dimension is <= 0, the row count exceeds 2^31 - 2^16, or a mask stride is negative */
+    TURBO_ERR_DTYPE = 3,  /* dtype is not TURBO_F32 / TURBO_F16 */
+    TURBO_ERR_ALIGN = 4,  /* a pointer is not aligned to its element size */
+    TURBO_ERR_LAUNCH = 5  /* HIP reported an error when the kernel was enqueued */
+};
+
+enum turbo_dtype {
+    TURBO_F32 = 0, /* IEEE binary32 in memory, binary32 arithmetic */
+    TURBO_F16 = 1  /* IEEE binary16 in memory, binary32 arithmetic; rounded to binary16 (nearest-even) only on the final store */
+};
+
+/*
+ * Scaled, masked softmax over attention scores (Section 2.1: the scaled
+ * dot-product attention applies a softmax to the query-key products;
+ * Section 4.1.2: softmax reduces a maximum and a sum over the low dimension).
+ *
+ *   scores[b,h,q,k] <- exp(z[b,h,q,k] - m) / sum_k exp(z[b,h,q,k] - m),
+ *   z = scale * scores + mask,   m = max_k z            (IN PLACE)
+ *
+ *   scores  device, [B,H,Sq,Sk] of `dtype`, read and overwritten.
+ *   mask    device, additive mask of the same dtype, dense [B,Sq,Sk], shared
+ *           by all heads (the padding mask of a zero-padded variable-length
+ *           batch, Section 2.1, holds 0 for real keys and -10000 for padded
+ *           ones).  NULL = no mask.  Must not overlap `scores`.
+ *   scale   multiplies the scores only; the mask is added unscaled.
+ *   dtype   TURBO_F32 or TURBO_F16.
+ *
+ * Masked entries come out as 0 because exp() underflows, not by a special
+ * case: a row whose keys are all masked is the softmax of its scores.
+ */
+int turbo_masked_softmax(void *scores, const void *mask, int B, int H, int Sq, int Sk, float scale, int dtype,
+                         void *stream);
+
+/*
+ * Same operation with explicit element strides for the mask, so compact
+ * masks need no expansion: mask element (b,q,k) is read from
+ * mask[b*mask_stride_b + q*mask_stride_q + k].
+ *   per-request key mask [B,Sk] : mask_stride_b = Sk,    mask_stride_q = 0
+ *   causal mask [Sq,Sk]         : mask_stride_b = 0,     mask_stride_q = Sk
+ *   dense [B,Sq,Sk]             : mask_stride_b = Sq*Sk, mask_stride_q = Sk
+ * Strides must be >= 0 (TURBO_ERR_SHAPE otherwise); they are ignored when
+ * mask is NULL.
+ */
+int turbo_masked_softmax_ex(void *scores, const void *mask, long long mask_stride_b, long long mask_stride_q, int B,
+                            int H, int Sq, int Sk, float scale, int dtype, void *stream);
+
+/*
+ * Fused bias add + residual add + LayerNorm (the "AddBiasLayerNorm" kernel of
+ * Section 6.2.1; Section 4.1.2 and Equation 1: LayerNorm reduces a mean and a
+ * population variance per row), binary32 tensors:
+ *
+ *   t[r,j]   = x[r,j] + bias[j] + residual[r,j]
+ *   mu_r     = mean_j t[r,j],   var_r = mean_j (t[r,j] - mu_r)^2
+ *   out[r,j] = (t[r,j] - mu_r) / sqrt(var_r + eps) * gamma[j] + beta[j]
+ *
+ *   x, residual, out   device, [rows, hidden]
+ *   bias, gamma, beta  device, [hidden]
+ *   residual and bias may be NULL (treated as zeros); x, gamma, beta, out
+ *   are required.  `out` may be exactly `x` or exactly `residual` (each row
+ *   is read completely before any of it is written); any other overlap is
+ *   undefined.
+ */
+int turbo_add_bias_layernorm(const void *x, const void *residual, const void *bias, const void *gamma,
+                             const void *beta, int rows, int hidden, float eps, void *out, void *stream);
+
+/* The same operation with all six tensors stored in `dtype` (TURBO_F32 or TURBO_F16). */
+int turbo_add_bias_layernorm_dt(const void *x, const void *residual, const void *bias, const void *gamma,
+                                const void *beta, int rows, int hidden, float eps, void *out, int dtype, void *stream);
+
+/* Static, NUL-terminated description of a status code (host pointer, never NULL). */
+const char *turbo_status_string(int status);
+
+/*
+ * Testing / tuning hooks.  Not needed for normal use, not thread-safe, and
+ * they never change what is computed, only which kernel variant computes it.
+ *
+ * turbo_set_override(key, value): value < 0 restores the built-in choice.
+ *   TURBO_OVR_PATH          force a kernel family: 0 wave (a group of lanes per
+ *                           row), 1 block (a workgroup per row, LDS combine),
+ *                           2 stream (a workgroup per row, row re-read from
+ *                           memory).  A forced family that cannot hold the
+ *                           row falls back to the built-in choice.
+ *   TURBO_OVR_MAX_VEC_BYTES cap the width of one load/store (2..16 bytes)
+ *   TURBO_OVR_GRID_WAVES    cap on resident workgroups per compute unit used to size the grid
+ * Returns TURBO_OK, or TURBO_ERR_SHAPE for an unknown key.
+ *
+ * turbo_describe_plan(op, rows, row_len, dtype, aligned16, buf, buf_len): writes
+ * a short text such as "wave vec=4 lanes=32 nv=1 rows=8" naming the variant the
+ * dispatcher would pick for `rows` rows of `row_len` elements (op 0 = softmax,
+ * 1 = layernorm).  `buf` is a HOST buffer.  Returns TURBO_OK or an error code.
+ *
+ * turbo_debug_fastdiv(n, d): the library's multiply-shift division n / d as the
+ * kernels compute it (host evaluation; n < 2^31, d >= 1), for host-side tests.
+ */
+enum turbo_override { TURBO_OVR_PATH = 0, TURBO_OVR_MAX_VEC_BYTES = 1, TURBO_OVR_GRID_WAVES = 2, TURBO_OVR_COUNT_ = 3 };
+int turbo_set_override(int key, int value);
+int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16, char *buf, int buf_len);
+unsigned turbo_debug_fastdiv(unsigned n, unsigned d);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TURBO_REDUCE_H */

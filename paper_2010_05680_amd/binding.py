@@ -1,0 +1,169 @@
+"""ctypes binding of libturbo_reduce.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point
+(include/turbo_reduce.h); tensors stand in for (pointer, sizes, dtype).  All
+arithmetic happens in the HIP kernels.  There is no CPU fallback: if the
+library has not been built, loading fails with an error that says how to
+build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libturbo_reduce.so")
+
+TURBO_OK, TURBO_ERR_NULL, TURBO_ERR_SHAPE, TURBO_ERR_DTYPE, TURBO_ERR_ALIGN, TURBO_ERR_LAUNCH = range(6)
+TURBO_F32, TURBO_F16 = 0, 1
+TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES = 0, 1, 2
+PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
+
+EXPORTED_SYMBOLS = (
+    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm", "turbo_add_bias_layernorm_dt",
+    "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
+)
+
+_lib = None
+
+
+class TurboError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library (raw entry points, for callers that hold device pointers themselves)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2010_05680_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, ll, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_float
+        L.turbo_masked_softmax.argtypes = [vp, vp, i, i, i, i, f, i, vp]
+        L.turbo_masked_softmax_ex.argtypes = [vp, vp, ll, ll, i, i, i, i, f, i, vp]
+        L.turbo_add_bias_layernorm.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, vp]
+        L.turbo_add_bias_layernorm_dt.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, i, vp]
+        for name in ("turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm",
+                     "turbo_add_bias_layernorm_dt", "turbo_set_override", "turbo_describe_plan"):
+            getattr(L, name).restype = i
+        L.turbo_status_string.argtypes = [i]
+        L.turbo_status_string.restype = ctypes.c_char_p
+        L.turbo_set_override.argtypes = [i, i]
+        L.turbo_describe_plan.argtypes = [i, i, i, i, i, ctypes.c_char_p, i]
+        L.turbo_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        L.turbo_debug_fastdiv.restype = ctypes.c_uint
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().turbo_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return TURBO_F32
+    if t.dtype == torch.float16:
+        return TURBO_F16
+    raise TypeError(f"unsupported dtype {t.dtype}: the library stores binary32 or binary16")
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != TURBO_OK:
+        raise TurboError(status, where)
+
+
+def turbo_masked_softmax(scores: torch.Tensor, mask: Optional[torch.Tensor], scale: float, stream=None) -> torch.Tensor:
+    """In-place softmax_k(scale*scores + mask) on [B,H,Sq,Sk]; mask is dense [B,Sq,Sk] or None."""
+    B, H, Sq, Sk = scores.shape
+    _dtype_code(scores)
+    if mask is not None:
+        if mask.dtype != scores.dtype or tuple(mask.shape) != (B, Sq, Sk):
+            raise ValueError("mask must be [B,Sq,Sk] in the scores' dtype")
+    _check(lib().turbo_masked_softmax(_dev_ptr(scores, "scores"), _dev_ptr(mask, "mask"), B, H, Sq, Sk, float(scale),
+                                      _dtype_code(scores), _stream_ptr(stream)), "turbo_masked_softmax")
+    return scores
+
+
+def turbo_masked_softmax_ex(scores: torch.Tensor, mask: Optional[torch.Tensor], mask_stride_b: int, mask_stride_q: int,
+                            scale: float, stream=None) -> torch.Tensor:
+    """In-place softmax with mask element (b,q,k) at mask[b*mask_stride_b + q*mask_stride_q + k]."""
+    B, H, Sq, Sk = scores.shape
+    _dtype_code(scores)
+    if mask is not None:
+        if mask.dtype != scores.dtype:
+            raise ValueError("mask must have the scores' dtype")
+        need = (B - 1) * mask_stride_b + (Sq - 1) * mask_stride_q + Sk
+        if mask_stride_b >= 0 and mask_stride_q >= 0 and mask.numel() < need:
+            raise ValueError("mask is smaller than its strides imply")
+    _check(lib().turbo_masked_softmax_ex(_dev_ptr(scores, "scores"), _dev_ptr(mask, "mask"), int(mask_stride_b),
+                                         int(mask_stride_q), B, H, Sq, Sk, float(scale), _dtype_code(scores),
+                                         _stream_ptr(stream)), "turbo_masked_softmax_ex")
+    return scores
+
+
+def _layernorm_args(x, residual, bias, gamma, beta, out):
+    rows, hidden = x.shape
+    _dtype_code(x)
+    for name, t, shape in (("residual", residual, (rows, hidden)), ("out", out, (rows, hidden)),
+                           ("bias", bias, (hidden,)), ("gamma", gamma, (hidden,)), ("beta", beta, (hidden,))):
+        if t is not None and (tuple(t.shape) != shape or t.dtype != x.dtype):
+            raise ValueError(f"{name} must be {shape} in x's dtype")
+    return rows, hidden
+
+
+def turbo_add_bias_layernorm(x, residual, bias, gamma, beta, eps: float, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """out = LayerNorm(x + bias + residual) * gamma + beta, binary32 tensors."""
+    if x.dtype != torch.float32:
+        raise TypeError("turbo_add_bias_layernorm is the binary32 entry point; use turbo_add_bias_layernorm_dt")
+    rows, hidden = _layernorm_args(x, residual, bias, gamma, beta, out)
+    _check(lib().turbo_add_bias_layernorm(_dev_ptr(x, "x"), _dev_ptr(residual, "residual"), _dev_ptr(bias, "bias"),
+                                          _dev_ptr(gamma, "gamma"), _dev_ptr(beta, "beta"), rows, hidden, float(eps),
+                                          _dev_ptr(out, "out"), _stream_ptr(stream)), "turbo_add_bias_layernorm")
+    return out
+
+
+def turbo_add_bias_layernorm_dt(x, residual, bias, gamma, beta, eps: float, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """The same with all tensors in x's dtype (binary32 or binary16 storage)."""
+    rows, hidden = _layernorm_args(x, residual, bias, gamma, beta, out)
+    _check(lib().turbo_add_bias_layernorm_dt(_dev_ptr(x, "x"), _dev_ptr(residual, "residual"), _dev_ptr(bias, "bias"),
+                                             _dev_ptr(gamma, "gamma"), _dev_ptr(beta, "beta"), rows, hidden,
+                                             float(eps), _dev_ptr(out, "out"), _dtype_code(x), _stream_ptr(stream)),
+           "turbo_add_bias_layernorm_dt")
+    return out
+
+
+def turbo_set_override(key: int, value: int) -> None:
+    _check(lib().turbo_set_override(int(key), int(value)), "turbo_set_override")
+
+
+def turbo_describe_plan(op: int, rows: int, row_len: int, dtype: int, aligned16: bool = True) -> str:
+    buf = ctypes.create_string_buffer(128)
+    _check(lib().turbo_describe_plan(int(op), int(rows), int(row_len), int(dtype), int(bool(aligned16)), buf, 128),
+           "turbo_describe_plan")
+    return buf.value.decode()

@@ -1,0 +1,519 @@
+// Fused bias + residual + LayerNorm kernels for gfx950 (wave64).
+//
+// Operation (Section 4.1.2, Equation 1, and the "AddBiasLayerNorm" kernel of
+// Section 6.2.1): t = x + bias + residual; per row the mean and the population
+// variance of t; out = (t - mean) / sqrt(var + eps) * gamma + beta.
+//
+// The paper reduces sum(x) and sum(x^2) together so that one synchronisation
+// yields both statistics.  The same "one exchange chain for both statistics"
+// holds here, but the pair that travels is the Welford state (mean, M2) merged
+// with Chan's rule: it is one pass as well and does not cancel when |mean| >> std.
+// The element counts behind each merge depend only on the lane and the row
+// length, so the merge weights are computed once per kernel, not per row.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "plan.h"
+#include "softmax_kernels.h"  // LaunchCfg, capped_grid, rows_in_flight_c
+
+namespace turbo {
+
+constexpr int kParamPreloadElems = 16;     // keep bias/gamma/beta in registers up to this many columns per lane
+
+struct LayerNormArgs {
+    const void* x;
+    const void* residual;  // may be null
+    const void* bias;      // may be null
+    const void* gamma;
+    const void* beta;
+    void* out;
+    int n_rows;
+    int hidden;
+    float eps;
+    float inv_hidden;
+};
+
+constexpr int log2_c(int g) { return g <= 1 ? 0 : 1 + log2_c(g / 2); }
+
+// Weights of the Chan merges along the exchange chain S = 1, 2, ..., G/2 for a
+// lane that holds `cnt` valid elements: after the call w1[i] = n_b/(n_a+n_b) and
+// w2[i] = n_a*n_b/(n_a+n_b) for step i, and the return value is the group total.
+template <int S, int G, int I, int N>
+__device__ __forceinline__ void merge_weights_step(float& n, float (&w1)[N], float (&w2)[N]) {
+    if constexpr (S < G) {
+        float na, nb;
+        exchange<S>(n, na, nb);
+        float nt = na + nb;
+        float inv = nt > 0.f ? 1.0f / nt : 0.f;
+        w1[I] = nb * inv;
+        w2[I] = na * nb * inv;
+        n = nt;
+        merge_weights_step<S * 2, G, I + 1, N>(n, w1, w2);
+    }
+}
+
+template <int S, int G, int I, int R, int N>
+__device__ __forceinline__ void merge_stats_step(float (&mean)[R], float (&m2)[R], const float (&w1)[N],
+                                                 const float (&w2)[N]) {
+    if constexpr (S < G) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float ma, mb, qa, qb;
+            exchange<S>(mean[r], ma, mb);
+            exchange<S>(m2[r], qa, qb);
+            float d = mb - ma;
+            mean[r] = fmaf(d, w1[I], ma);
+            m2[r] = fmaf(d * d, w2[I], qa + qb);
+        }
+        merge_stats_step<S * 2, G, I + 1, R, N>(mean, m2, w1, w2);
+    }
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_param(const T* p, int col, bool ok, float (&dst)[VEC], float fill) {
+    if (p != nullptr && ok) {
+        Pack<T, VEC> raw = load_pack<T, VEC>(p + col);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) dst[j] = (float)raw.v[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) dst[j] = fill;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// wave family: G lanes per row, NV vectors per lane, R rows per lane group.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int G, int NV, bool RES>
+__global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
+    constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
+    constexpr int GPW = kWave / G;
+    constexpr int kWaves = 4;
+    constexpr int TILE_ROWS = R * GPW * kWaves;
+    constexpr int STEPS = log2_c(G) > 0 ? log2_c(G) : 1;
+    constexpr bool PRELOAD = NV * VEC <= kParamPreloadElems;
+
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    const T* __restrict__ gamma = reinterpret_cast<const T*>(a.gamma);
+    const T* __restrict__ beta = reinterpret_cast<const T*>(a.beta);
+    T* out = reinterpret_cast<T*>(a.out);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int gl = lane % G;
+    const int grp = lane / G;
+    const int hidden = a.hidden;
+
+    float cnt = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+        if ((v * G + gl) * VEC < hidden) cnt += (float)VEC;
+    const float inv_cnt = cnt > 0.f ? 1.0f / cnt : 0.f;
+    float w1[STEPS], w2[STEPS];
+    {
+        float n = cnt;
+        merge_weights_step<1, G, 0, STEPS>(n, w1, w2);
+    }
+
+    float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
+    if constexpr (PRELOAD) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * G + gl) * VEC;
+            bool ok = col < hidden;
+            load_param<T, VEC>(bias, col, ok, pb[v], 0.f);
+            load_param<T, VEC>(gamma, col, ok, pg[v], 0.f);
+            load_param<T, VEC>(beta, col, ok, pe[v], 0.f);
+        }
+    }
+
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
+
+        Pack<T, VEC> xr[R][NV];
+        Pack<T, VEC> rr[R][NV];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int row = row_base + r * GPW;
+            int rowc = row < a.n_rows ? row : a.n_rows - 1;
+            const long long off = (long long)rowc * hidden;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int col = (v * G + gl) * VEC;
+                int colc = col < hidden ? col : 0;
+                xr[r][v] = load_pack<T, VEC>(x + off + colc);
+                if constexpr (RES) rr[r][v] = load_pack<T, VEC>(res + off + colc);
+            }
+        }
+
+        float t[R][NV][VEC];
+        float mean[R], m2[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int col = (v * G + gl) * VEC;
+                const bool ok = col < hidden;
+                float b[VEC];
+                if constexpr (PRELOAD) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) b[j] = pb[v][j];
+                } else {
+                    load_param<T, VEC>(bias, col, ok, b, 0.f);
+                }
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float tv = (float)xr[r][v].v[j] + b[j];
+                    if constexpr (RES) tv += (float)rr[r][v].v[j];
+                    tv = ok ? tv : 0.f;
+                    t[r][v][j] = tv;
+                    sum += tv;
+                }
+            }
+            const float mu = sum * inv_cnt;
+            float q = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const bool ok = (v * G + gl) * VEC < hidden;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float d = t[r][v][j] - mu;
+                    q += ok ? d * d : 0.f;
+                }
+            }
+            mean[r] = mu;
+            m2[r] = q;
+        }
+        merge_stats_step<1, G, 0, R, STEPS>(mean, m2, w1, w2);
+
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int row = row_base + r * GPW;
+            const float rstd = fast_rsqrt(fmaf(m2[r], a.inv_hidden, a.eps));
+            T* op = out + (long long)row * hidden;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int col = (v * G + gl) * VEC;
+                if (row < a.n_rows && col < hidden) {
+                    float g[VEC], be[VEC];
+                    if constexpr (PRELOAD) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) {
+                            g[j] = pg[v][j];
+                            be[j] = pe[v][j];
+                        }
+                    } else {
+                        load_param<T, VEC>(gamma, col, true, g, 0.f);
+                        load_param<T, VEC>(beta, col, true, be, 0.f);
+                    }
+                    Pack<T, VEC> o;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o.v[j] = (T)fmaf((t[r][v][j] - mean[r]) * rstd, g[j], be[j]);
+                    store_pack<T, VEC>(op + col, o);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Cross-wavefront combine of (count, mean, M2) through LDS, one barrier per row.
+// ---------------------------------------------------------------------------
+struct LayerNormLds {
+    float n[2][kBlockMaxWaves];
+    float mean[2][kBlockMaxWaves];
+    float m2[2][kBlockMaxWaves];
+};
+
+__device__ __forceinline__ void layernorm_block_combine(LayerNormLds& lds, int slot, int wave, int lane, int n_waves,
+                                                        float n_w, float& mean, float& m2) {
+    if (lane == 0) {
+        lds.n[slot][wave] = n_w;
+        lds.mean[slot][wave] = mean;
+        lds.m2[slot][wave] = m2;
+    }
+    __syncthreads();
+    float n = 0.f, mu = 0.f, q = 0.f;
+    for (int w = 0; w < n_waves; ++w) {
+        float nb = lds.n[slot][w];
+        float nt = n + nb;
+        float inv = fast_rcp(fmaxf(nt, 1.f));
+        float d = lds.mean[slot][w] - mu;
+        mu = fmaf(d, nb * inv, mu);
+        q = fmaf(d * d, n * nb * inv, q + lds.m2[slot][w]);
+        n = nt;
+    }
+    mean = mu;
+    m2 = q;
+}
+
+// block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
+template <typename T, int VEC, int NV, bool RES>
+__global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) {
+    __shared__ LayerNormLds lds;
+    constexpr bool PRELOAD = NV * VEC <= kParamPreloadElems;
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    const T* __restrict__ gamma = reinterpret_cast<const T*>(a.gamma);
+    const T* __restrict__ beta = reinterpret_cast<const T*>(a.beta);
+    T* out = reinterpret_cast<T*>(a.out);
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int hidden = a.hidden;
+    const int bd = (int)blockDim.x;
+
+    float cnt = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+        if ((v * bd + tid) * VEC < hidden) cnt += (float)VEC;
+    const float inv_cnt = cnt > 0.f ? 1.0f / cnt : 0.f;
+    float w1[6], w2[6];
+    float n_w = cnt;
+    merge_weights_step<1, kWave, 0, 6>(n_w, w1, w2);
+
+    float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
+    if constexpr (PRELOAD) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * bd + tid) * VEC;
+            bool ok = col < hidden;
+            load_param<T, VEC>(bias, col, ok, pb[v], 0.f);
+            load_param<T, VEC>(gamma, col, ok, pg[v], 0.f);
+            load_param<T, VEC>(beta, col, ok, pe[v], 0.f);
+        }
+    }
+
+    int slot = 0;
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+        const long long off = (long long)row * hidden;
+        Pack<T, VEC> xr[NV];
+        Pack<T, VEC> rr[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * bd + tid) * VEC;
+            int colc = col < hidden ? col : 0;
+            xr[v] = load_pack<T, VEC>(x + off + colc);
+            if constexpr (RES) rr[v] = load_pack<T, VEC>(res + off + colc);
+        }
+
+        float t[NV][VEC];
+        float sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * bd + tid) * VEC;
+            const bool ok = col < hidden;
+            float b[VEC];
+            if constexpr (PRELOAD) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) b[j] = pb[v][j];
+            } else {
+                load_param<T, VEC>(bias, col, ok, b, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float tv = (float)xr[v].v[j] + b[j];
+                if constexpr (RES) tv += (float)rr[v].v[j];
+                tv = ok ? tv : 0.f;
+                t[v][j] = tv;
+                sum += tv;
+            }
+        }
+        float mean[1] = {sum * inv_cnt};
+        float m2[1] = {0.f};
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const bool ok = (v * bd + tid) * VEC < hidden;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float d = t[v][j] - mean[0];
+                m2[0] += ok ? d * d : 0.f;
+            }
+        }
+        merge_stats_step<1, kWave, 0, 1, 6>(mean, m2, w1, w2);
+        layernorm_block_combine(lds, slot, wave, lane, n_waves, n_w, mean[0], m2[0]);
+        const float rstd = fast_rsqrt(fmaf(m2[0], a.inv_hidden, a.eps));
+
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * bd + tid) * VEC;
+            if (col < hidden) {
+                float g[VEC], be[VEC];
+                if constexpr (PRELOAD) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        g[j] = pg[v][j];
+                        be[j] = pe[v][j];
+                    }
+                } else {
+                    load_param<T, VEC>(gamma, col, true, g, 0.f);
+                    load_param<T, VEC>(beta, col, true, be, 0.f);
+                }
+                Pack<T, VEC> o;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) o.v[j] = (T)fmaf((t[v][j] - mean[0]) * rstd, g[j], be[j]);
+                store_pack<T, VEC>(out + off + col, o);
+            }
+        }
+    }
+}
+
+// stream family: rows too long for registers; statistics in a first sweep
+// (running Welford state per lane, merged chunk by chunk), output in a second.
+template <typename T, int VEC, bool RES>
+__global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerNormArgs a) {
+    __shared__ LayerNormLds lds;
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    const T* __restrict__ gamma = reinterpret_cast<const T*>(a.gamma);
+    const T* __restrict__ beta = reinterpret_cast<const T*>(a.beta);
+    T* out = reinterpret_cast<T*>(a.out);
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int hidden = a.hidden;
+    const long long step = (long long)blockDim.x * VEC;
+
+    float cnt = 0.f;
+    for (long long col = (long long)tid * VEC; col < hidden; col += step) cnt += (float)VEC;
+    float w1[6], w2[6];
+    float n_w = cnt;
+    merge_weights_step<1, kWave, 0, 6>(n_w, w1, w2);
+
+    int slot = 0;
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+        const long long off = (long long)row * hidden;
+        float n_run = 0.f, mu_run = 0.f, q_run = 0.f;
+        for (long long col = (long long)tid * VEC; col < hidden; col += step) {
+            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);
+            Pack<T, VEC> rr;
+            if constexpr (RES) rr = load_pack<T, VEC>(res + off + col);
+            float b[VEC];
+            load_param<T, VEC>(bias, (int)col, true, b, 0.f);
+            float t[VEC];
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                t[j] = (float)xr.v[j] + b[j];
+                if constexpr (RES) t[j] += (float)rr.v[j];
+                s += t[j];
+            }
+            const float cm = s * (1.0f / VEC);
+            float cq = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) cq += (t[j] - cm) * (t[j] - cm);
+            const float nt = n_run + (float)VEC;
+            const float inv = fast_rcp(nt);
+            const float d = cm - mu_run;
+            mu_run = fmaf(d, (float)VEC * inv, mu_run);
+            q_run = fmaf(d * d, n_run * (float)VEC * inv, q_run + cq);
+            n_run = nt;
+        }
+        float mean[1] = {mu_run};
+        float m2[1] = {q_run};
+        merge_stats_step<1, kWave, 0, 1, 6>(mean, m2, w1, w2);
+        layernorm_block_combine(lds, slot, wave, lane, n_waves, n_w, mean[0], m2[0]);
+        const float rstd = fast_rsqrt(fmaf(m2[0], a.inv_hidden, a.eps));
+
+        for (long long col = (long long)tid * VEC; col < hidden; col += step) {
+            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);
+            Pack<T, VEC> rr;
+            if constexpr (RES) rr = load_pack<T, VEC>(res + off + col);
+            float b[VEC], g[VEC], be[VEC];
+            load_param<T, VEC>(bias, (int)col, true, b, 0.f);
+            load_param<T, VEC>(gamma, (int)col, true, g, 0.f);
+            load_param<T, VEC>(beta, (int)col, true, be, 0.f);
+            Pack<T, VEC> o;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float tv = (float)xr.v[j] + b[j];
+                if constexpr (RES) tv += (float)rr.v[j];
+                o.v[j] = (T)fmaf((tv - mean[0]) * rstd, g[j], be[j]);
+            }
+            store_pack<T, VEC>(out + off + col, o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host-side launch
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int G, int NV, bool RES>
+hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
+    constexpr int TILE_ROWS = R * (kWave / G) * 4;
+    int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
+    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES>), dim3(capped_grid(n_tiles, lc)), dim3(256), 0, s, a,
+                       n_tiles);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, int NV, bool RES>
+hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    LaunchCfg c = lc;
+    c.blocks_per_cu = lc.blocks_per_cu * 4 / p.waves > 0 ? lc.blocks_per_cu * 4 / p.waves : 1;
+    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES>), dim3(capped_grid(a.n_rows, c)), dim3(64 * p.waves), 0,
+                       s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, bool RES>
+hipError_t launch_layernorm_vr(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    if (p.path == kPathWave) {
+        if (p.lanes < 64) {
+            switch (p.lanes) {
+                case 4: return launch_layernorm_wave<T, VEC, 4, 1, RES>(a, lc, s);
+                case 8: return launch_layernorm_wave<T, VEC, 8, 1, RES>(a, lc, s);
+                case 16: return launch_layernorm_wave<T, VEC, 16, 1, RES>(a, lc, s);
+                case 32: return launch_layernorm_wave<T, VEC, 32, 1, RES>(a, lc, s);
+            }
+            return hipErrorInvalidValue;
+        }
+        switch (p.nv) {
+            case 1: if constexpr (1 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 1, RES>(a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 2, RES>(a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 3, RES>(a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 4, RES>(a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 6, RES>(a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 8, RES>(a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 12, RES>(a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 16, RES>(a, lc, s); else break;
+        }
+        return hipErrorInvalidValue;
+    }
+    if (p.path == kPathBlock) {
+        switch (p.nv) {
+            case 1: if constexpr (1 * VEC <= kLayerNormLimits.block_max_epl || 1 == 1) return launch_layernorm_block<T, VEC, 1, RES>(p, a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kLayerNormLimits.block_max_epl || 2 == 1) return launch_layernorm_block<T, VEC, 2, RES>(p, a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kLayerNormLimits.block_max_epl || 3 == 1) return launch_layernorm_block<T, VEC, 3, RES>(p, a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kLayerNormLimits.block_max_epl || 4 == 1) return launch_layernorm_block<T, VEC, 4, RES>(p, a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kLayerNormLimits.block_max_epl || 6 == 1) return launch_layernorm_block<T, VEC, 6, RES>(p, a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kLayerNormLimits.block_max_epl || 8 == 1) return launch_layernorm_block<T, VEC, 8, RES>(p, a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kLayerNormLimits.block_max_epl || 12 == 1) return launch_layernorm_block<T, VEC, 12, RES>(p, a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kLayerNormLimits.block_max_epl || 16 == 1) return launch_layernorm_block<T, VEC, 16, RES>(p, a, lc, s); else break;
+        }
+        return hipErrorInvalidValue;
+    }
+    LaunchCfg c = lc;
+    c.blocks_per_cu = 2;
+    hipLaunchKernelGGL((layernorm_stream_kernel<T, VEC, RES>), dim3(capped_grid(a.n_rows, c)), dim3(kStreamThreads), 0,
+                       s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t launch_layernorm_v(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    return a.residual ? launch_layernorm_vr<T, VEC, true>(p, a, lc, s) : launch_layernorm_vr<T, VEC, false>(p, a, lc, s);
+}
+
+hipError_t launch_layernorm_f32(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s);
+hipError_t launch_layernorm_f16(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s);
+
+}  // namespace turbo

@@ -1,0 +1,152 @@
+// Host-side choice of kernel variant from row length, element size and alignment.
+// Plain C++ (no HIP), shared by the launchers and by turbo_describe_plan().
+//
+// Three families, chosen by row length (the paper assigns rows to thread blocks
+// and splits a block's work over warps, Section 4.1.2; here the split is chosen
+// per call because the row length is shared by the whole batch):
+//   wave   : an aligned group of G lanes (4..64) owns a row and keeps it in
+//            registers; a wavefront works on R * (64/G) rows at once.
+//   block  : a workgroup of W wavefronts owns a row; per-wavefront partial
+//            results are combined through LDS with one barrier.
+//   stream : a workgroup owns a row too long for registers and reads it twice.
+#pragma once
+#include <cstdio>
+
+namespace turbo {
+
+enum PathKind { kPathWave = 0, kPathBlock = 1, kPathStream = 2 };
+
+constexpr int kMaxNV = 16;                 // most vectors a lane keeps in registers
+constexpr int kWaveMaxVecs = 64 * kMaxNV;  // longest row (in vectors) a single wavefront may own
+constexpr int kBlockMaxWaves = 16;
+constexpr int kStreamThreads = 1024;
+
+// Register budgets, in row elements held per lane, that bound each family.
+struct OpLimits {
+    int target_elems;    // wave: rows in flight are chosen so a lane holds about this many values
+    int wave_max_epl;    // wave: most elements of one row per lane
+    int block_pref_epl;  // block: grow the workgroup until a lane holds at most this many
+    int block_max_epl;   // block: most elements per lane at 16 wavefronts (1024 threads, 128 VGPRs)
+};
+constexpr OpLimits kSoftmaxLimits{32, 64, 16, 32};
+constexpr OpLimits kLayerNormLimits{16, 24, 16, 16};
+
+struct Plan {
+    int path;    // PathKind
+    int vec;     // elements per load/store
+    int lanes;   // wave: lanes per row (G)
+    int nv;      // vectors per lane
+    int rows;    // wave: rows a lane group works on concurrently (R)
+    int waves;   // block: wavefronts per row (W)
+};
+
+struct Overrides {
+    int path = -1;
+    int max_vec_bytes = -1;
+    int grid_waves = -1;
+};
+
+inline int round_up_nv(int nv) {
+    static const int supported[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    for (int s : supported)
+        if (nv <= s) return s;
+    return -1;
+}
+
+inline int pow2_ceil(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Rows in flight per lane group so that a lane holds about `target_elems` values.
+inline int rows_in_flight(int nv, int vec, int target_elems) {
+    int r = target_elems / (nv * vec);
+    if (r >= 8) return 8;
+    if (r >= 4) return 4;
+    if (r >= 2) return 2;
+    return 1;
+}
+
+// align_elems: largest power of two (in elements) to which every base pointer and
+// every row start is aligned; the vector width never exceeds it.
+inline Plan make_plan(int row_len, int elem_size, long long align_elems, long long n_rows, const OpLimits& lim,
+                      const Overrides& ovr) {
+    Plan p{};
+    int vec_bytes = 16;
+    if (ovr.max_vec_bytes >= elem_size && ovr.max_vec_bytes < 16) vec_bytes = ovr.max_vec_bytes;
+    int vec = vec_bytes / elem_size;
+    while (vec > 1 && (row_len % vec != 0 || align_elems % vec != 0)) vec >>= 1;
+    p.vec = vec;
+    const long long nvec = row_len / vec;
+
+    // wave family: feasible when one wavefront's registers hold the row
+    bool wave_ok = false;
+    int wave_g = 0, wave_nv = 0;
+    if (nvec <= kWaveMaxVecs) {
+        int g = pow2_ceil((int)nvec);
+        if (g < 4) g = 4;
+        if (g > 64) g = 64;
+        int nv = round_up_nv((int)((nvec + g - 1) / g));
+        if (nv > 0 && nv * vec <= lim.wave_max_epl) {
+            wave_ok = true;
+            wave_g = g;
+            wave_nv = nv;
+        }
+    }
+    // block family: smallest workgroup that meets the preferred budget, else 16 wavefronts
+    bool block_ok = false;
+    int block_w = 0, block_nv = 0;
+    for (int w = 2; w <= kBlockMaxWaves; w *= 2) {
+        long long per_lane = (nvec + 64 * w - 1) / (64 * w);
+        if (per_lane > kMaxNV) continue;
+        int nv = round_up_nv((int)per_lane);
+        int budget = w < kBlockMaxWaves ? lim.block_pref_epl : lim.block_max_epl;
+        if (nv * vec <= budget || (nv == 1 && w == 2)) {
+            block_ok = true;
+            block_w = w;
+            block_nv = nv;
+            break;
+        }
+    }
+
+    int path;
+    if (wave_ok) {
+        // Long rows with few of them: a workgroup per row exposes more parallelism.
+        path = (block_ok && nvec >= 512 && n_rows < 4096) ? kPathBlock : kPathWave;
+    } else {
+        path = block_ok ? kPathBlock : kPathStream;
+    }
+    if (ovr.path == kPathWave && wave_ok) path = kPathWave;
+    if (ovr.path == kPathBlock && block_ok) path = kPathBlock;
+    if (ovr.path == kPathStream) path = kPathStream;
+    p.path = path;
+
+    if (path == kPathWave) {
+        p.lanes = wave_g;
+        p.nv = wave_nv;
+        p.rows = rows_in_flight(p.nv, vec, lim.target_elems);
+        p.waves = 4;
+    } else if (path == kPathBlock) {
+        p.waves = block_w;
+        p.lanes = 64;
+        p.nv = block_nv;
+        p.rows = 1;
+    } else {
+        p.waves = kStreamThreads / 64;
+        p.lanes = 64;
+        p.nv = 1;
+        p.rows = 1;
+    }
+    return p;
+}
+
+inline void describe_plan(const Plan& p, char* buf, int n) {
+    static const char* names[] = {"wave", "block", "stream"};
+    if (p.path == kPathWave)
+        std::snprintf(buf, n, "%s vec=%d lanes=%d nv=%d rows=%d", names[p.path], p.vec, p.lanes, p.nv, p.rows);
+    else
+        std::snprintf(buf, n, "%s vec=%d waves=%d nv=%d", names[p.path], p.vec, p.waves, p.nv);
+}
+
+}  // namespace turbo

@@ -1,0 +1,16 @@
+// binary16-storage instantiations of the masked softmax kernels (binary32 arithmetic).
+#include "softmax_kernels.h"
+
+namespace turbo {
+
+hipError_t launch_softmax_f16(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    switch (p.vec) {
+        case 8: return launch_softmax_v<_Float16, 8>(p, a, lc, s);
+        case 4: return launch_softmax_v<_Float16, 4>(p, a, lc, s);
+        case 2: return launch_softmax_v<_Float16, 2>(p, a, lc, s);
+        case 1: return launch_softmax_v<_Float16, 1>(p, a, lc, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace turbo

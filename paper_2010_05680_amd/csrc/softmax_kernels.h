@@ -1,0 +1,412 @@
+// Scaled, masked softmax kernels for gfx950 (wave64).
+//
+// Operation (Sections 2.1 and 4.1.2 of the paper): for every row of the 2-D view
+// [B*H*Sq, Sk] of the attention scores, z = scale*s + mask, then a maximum and a
+// sum over the row, then exp(z - max)/sum written back in place.
+//
+// Every element crosses HBM once in and once out: a row lives in registers
+// between the load and the store (wave and block families).  The maximum and the
+// sum are reduced with DPP / permlane exchanges; R rows are reduced together so
+// their exchange chains interleave (the paper's "reduce X rows at once" idea,
+// re-derived for 64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "plan.h"
+
+namespace turbo {
+
+
+struct SoftmaxArgs {
+    void* scores;
+    const void* mask;
+    long long mask_stride_b;
+    long long mask_stride_q;
+    int n_rows;      // B*H*Sq
+    int Sq;
+    int Sk;
+    float scale;
+    FastDiv div_rows_per_batch;  // H*Sq
+    FastDiv div_sq;              // Sq
+};
+
+struct LaunchCfg {
+    int num_cus;
+    int blocks_per_cu;  // cap on the grid, in workgroups per compute unit
+};
+
+constexpr int rows_in_flight_c(int nv, int vec, int target) {
+    int r = target / (nv * vec);
+    return r >= 8 ? 8 : r >= 4 ? 4 : r >= 2 ? 2 : 1;
+}
+
+template <typename T, bool MASK>
+__device__ __forceinline__ const T* mask_row_ptr(const SoftmaxArgs& a, int row) {
+    if constexpr (MASK) {
+        unsigned b = fastdiv((unsigned)row, a.div_rows_per_batch);
+        unsigned q = (unsigned)row - fastdiv((unsigned)row, a.div_sq) * (unsigned)a.Sq;
+        return reinterpret_cast<const T*>(a.mask) + (long long)b * a.mask_stride_b + (long long)q * a.mask_stride_q;
+    } else {
+        return nullptr;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// wave family: G lanes per row, NV vectors per lane, R rows per lane group.
+// Lane `gl` of a group holds vectors gl, gl+G, gl+2G, ... of its row, so one load
+// instruction of a wavefront covers 64/G consecutive rows in 16*G-byte pieces.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int G, int NV, bool MASK>
+__global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
+    constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
+    constexpr int GPW = kWave / G;  // lane groups per wavefront
+    constexpr int kWaves = 4;
+    constexpr int TILE_ROWS = R * GPW * kWaves;
+
+    T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int gl = lane % G;
+    const int grp = lane / G;
+    const int Sk = a.Sk;
+    const float scale = a.scale;
+
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
+
+        Pack<T, VEC> raw[R][NV];
+        Pack<T, VEC> mraw[R][NV];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int row = row_base + r * GPW;
+            int rowc = row < a.n_rows ? row : a.n_rows - 1;  // out-of-range rows recompute the last row, unstored
+            const T* rp = scores + (long long)rowc * Sk;
+            const T* mp = mask_row_ptr<T, MASK>(a, rowc);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int col = (v * G + gl) * VEC;
+                int colc = col < Sk ? col : 0;
+                raw[r][v] = load_pack<T, VEC>(rp + colc);
+                if constexpr (MASK) mraw[r][v] = load_pack<T, VEC>(mp + colc);
+            }
+        }
+
+        float z[R][NV][VEC];
+        float m[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            m[r] = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const bool ok = (v * G + gl) * VEC < Sk;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float s = (float)raw[r][v].v[j];
+                    float t;
+                    if constexpr (MASK)
+                        t = fmaf(s, scale, (float)mraw[r][v].v[j]);
+                    else
+                        t = s * scale;
+                    t = ok ? t : -INFINITY;
+                    z[r][v][j] = t;
+                    m[r] = fmaxf(m[r], t);
+                }
+            }
+        }
+        group_allreduce<G, R>(m, MaxOp{});
+
+        float l[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float shift = -m[r] * kLog2e;
+            l[r] = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float e = fast_exp2(fmaf(z[r][v][j], kLog2e, shift));
+                    z[r][v][j] = e;
+                    l[r] += e;
+                }
+        }
+        group_allreduce<G, R>(l, SumOp{});
+
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int row = row_base + r * GPW;
+            const float inv = fast_rcp(l[r]);
+            T* rp = scores + (long long)row * Sk;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int col = (v * G + gl) * VEC;
+                if (row < a.n_rows && col < Sk) {
+                    Pack<T, VEC> o;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
+                    store_pack<T, VEC>(rp + col, o);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Cross-wavefront combine of (max, sum-of-exp) pairs through LDS.
+// Each wavefront publishes the maximum it saw and its sum taken relative to that
+// maximum; one barrier later every lane rebuilds the row's maximum M and sum L
+// and the factor that rescales its own exponentials: exp(m_w - M) / L.
+// Two LDS slots alternate between consecutive rows so one barrier per row is enough.
+// ---------------------------------------------------------------------------
+struct SoftmaxLds {
+    float m[2][kBlockMaxWaves];
+    float l[2][kBlockMaxWaves];
+};
+
+__device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot, int wave, int lane, int n_waves,
+                                                       float m_w, float l_w) {
+    if (lane == 0) {
+        lds.m[slot][wave] = m_w;
+        lds.l[slot][wave] = l_w;
+    }
+    __syncthreads();
+    float M = -INFINITY;
+    for (int w = 0; w < n_waves; ++w) M = fmaxf(M, lds.m[slot][w]);
+    float L = 0.f;
+    for (int w = 0; w < n_waves; ++w) L += lds.l[slot][w] * fast_exp2((lds.m[slot][w] - M) * kLog2e);
+    return fast_exp2((m_w - M) * kLog2e) * fast_rcp(L);  // a wavefront that saw no element has m_w = -inf: factor 0
+}
+
+// block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
+template <typename T, int VEC, int NV, bool MASK>
+__global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
+    __shared__ SoftmaxLds lds;
+    T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int Sk = a.Sk;
+    const float scale = a.scale;
+
+    int slot = 0;
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+        T* rp = scores + (long long)row * Sk;
+        const T* mp = mask_row_ptr<T, MASK>(a, row);
+
+        Pack<T, VEC> raw[NV];
+        Pack<T, VEC> mraw[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * (int)blockDim.x + tid) * VEC;
+            int colc = col < Sk ? col : 0;
+            raw[v] = load_pack<T, VEC>(rp + colc);
+            if constexpr (MASK) mraw[v] = load_pack<T, VEC>(mp + colc);
+        }
+
+        float z[NV][VEC];
+        float m[1] = {-INFINITY};
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const bool ok = (v * (int)blockDim.x + tid) * VEC < Sk;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float s = (float)raw[v].v[j];
+                float t;
+                if constexpr (MASK)
+                    t = fmaf(s, scale, (float)mraw[v].v[j]);
+                else
+                    t = s * scale;
+                t = ok ? t : -INFINITY;
+                z[v][j] = t;
+                m[0] = fmaxf(m[0], t);
+            }
+        }
+        group_allreduce<kWave, 1>(m, MaxOp{});
+        const float m_w = m[0];
+        const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
+
+        float l[1] = {0.f};
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float e = fast_exp2(fmaf(z[v][j], kLog2e, shift));
+                z[v][j] = e;
+                l[0] += e;
+            }
+        group_allreduce<kWave, 1>(l, SumOp{});
+
+        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
+
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int col = (v * (int)blockDim.x + tid) * VEC;
+            if (col < Sk) {
+                Pack<T, VEC> o;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[v][j] * f);
+                store_pack<T, VEC>(rp + col, o);
+            }
+        }
+    }
+}
+
+// stream family: rows too long for registers.  First sweep keeps a running
+// (max, sum) per lane, rescaling the sum whenever the maximum grows; after the
+// combine a second sweep re-reads the row and writes the result.
+template <typename T, int VEC, bool MASK>
+__global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxArgs a) {
+    __shared__ SoftmaxLds lds;
+    T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int Sk = a.Sk;
+    const float scale = a.scale;
+    const int step = (int)blockDim.x * VEC;
+
+    int slot = 0;
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+        T* rp = scores + (long long)row * Sk;
+        const T* mp = mask_row_ptr<T, MASK>(a, row);
+
+        float m_run = -INFINITY, l_run = 0.f;
+        for (long long col = (long long)tid * VEC; col < Sk; col += step) {
+            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);
+            Pack<T, VEC> mraw;
+            if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
+            float z[VEC];
+            float cm = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float s = (float)raw.v[j];
+                if constexpr (MASK)
+                    z[j] = fmaf(s, scale, (float)mraw.v[j]);
+                else
+                    z[j] = s * scale;
+                cm = fmaxf(cm, z[j]);
+            }
+            if (cm > m_run) {
+                l_run *= fast_exp2((m_run - cm) * kLog2e);  // first chunk: 0 * exp2(-inf) = 0
+                m_run = cm;
+            }
+            const float shift = -m_run * kLog2e;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) l_run += fast_exp2(fmaf(z[j], kLog2e, shift));
+        }
+
+        float m[1] = {m_run};
+        group_allreduce<kWave, 1>(m, MaxOp{});
+        const float m_w = m[0];
+        float l[1];
+        l[0] = (m_run == -INFINITY) ? 0.f : l_run * fast_exp2((m_run - m_w) * kLog2e);
+        group_allreduce<kWave, 1>(l, SumOp{});
+
+        // factor = exp(m_w - M) / L; the second sweep needs exp(z - M)/L, so fold m_w back in
+        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
+        // exp2((z - m_w) log2e) * f == exp(z - M)/L; a wavefront with no element stores nothing
+        const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
+        for (long long col = (long long)tid * VEC; col < Sk; col += step) {
+            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);
+            Pack<T, VEC> mraw;
+            if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
+            Pack<T, VEC> o;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                float s = (float)raw.v[j];
+                float zz;
+                if constexpr (MASK)
+                    zz = fmaf(s, scale, (float)mraw.v[j]);
+                else
+                    zz = s * scale;
+                o.v[j] = (T)(fast_exp2(fmaf(zz, kLog2e, shift)) * f);
+            }
+            store_pack<T, VEC>(rp + col, o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host-side launch
+// ---------------------------------------------------------------------------
+inline int capped_grid(long long work_items, const LaunchCfg& lc) {
+    long long cap = (long long)lc.num_cus * lc.blocks_per_cu;
+    long long g = work_items < cap ? work_items : cap;
+    return (int)(g < 1 ? 1 : g);
+}
+
+template <typename T, int VEC, int G, int NV, bool MASK>
+hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
+    constexpr int TILE_ROWS = R * (kWave / G) * 4;
+    int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
+    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK>), dim3(capped_grid(n_tiles, lc)), dim3(256), 0, s, a,
+                       n_tiles);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, int NV, bool MASK>
+hipError_t launch_softmax_block(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    LaunchCfg c = lc;
+    c.blocks_per_cu = lc.blocks_per_cu * 4 / p.waves > 0 ? lc.blocks_per_cu * 4 / p.waves : 1;
+    hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MASK>), dim3(capped_grid(a.n_rows, c)), dim3(64 * p.waves), 0,
+                       s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC, bool MASK>
+hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    if (p.path == kPathWave) {
+        if (p.lanes < 64) {
+            switch (p.lanes) {
+                case 4: return launch_softmax_wave<T, VEC, 4, 1, MASK>(a, lc, s);
+                case 8: return launch_softmax_wave<T, VEC, 8, 1, MASK>(a, lc, s);
+                case 16: return launch_softmax_wave<T, VEC, 16, 1, MASK>(a, lc, s);
+                case 32: return launch_softmax_wave<T, VEC, 32, 1, MASK>(a, lc, s);
+            }
+            return hipErrorInvalidValue;
+        }
+        switch (p.nv) {
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 1, MASK>(a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 2, MASK>(a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 3, MASK>(a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 4, MASK>(a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 6, MASK>(a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 8, MASK>(a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 12, MASK>(a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 16, MASK>(a, lc, s); else break;
+        }
+        return hipErrorInvalidValue;
+    }
+    if (p.path == kPathBlock) {
+        switch (p.nv) {
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MASK>(p, a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MASK>(p, a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MASK>(p, a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MASK>(p, a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MASK>(p, a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MASK>(p, a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MASK>(p, a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MASK>(p, a, lc, s); else break;
+        }
+        return hipErrorInvalidValue;
+    }
+    LaunchCfg c = lc;
+    c.blocks_per_cu = 2;
+    hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MASK>), dim3(capped_grid(a.n_rows, c)), dim3(kStreamThreads), 0, s,
+                       a);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t launch_softmax_v(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    return a.mask ? launch_softmax_vm<T, VEC, true>(p, a, lc, s) : launch_softmax_vm<T, VEC, false>(p, a, lc, s);
+}
+
+// Defined once per element type in softmax_f32.hip / softmax_f16.hip.
+hipError_t launch_softmax_f32(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s);
+hipError_t launch_softmax_f16(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s);
+
+}  // namespace turbo

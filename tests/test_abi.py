@@ -1,0 +1,127 @@
+"""Host-side tests of the C ABI: the library loads, exports what the header declares,
+and rejects bad arguments before touching the GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2010_05680_amd import binding as tb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "turbo_reduce.h")
+
+FAKE = 0x10000  # a non-null, 16-byte aligned "device pointer"; validation must fail before it is used
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(turbo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = tb.lib()
+    declared = _declared_functions()
+    assert set(declared) == set(tb.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name), f"{name} is declared in turbo_reduce.h but not exported"
+
+
+def test_status_strings():
+    assert tb.status_string(tb.TURBO_OK) == "ok"
+    seen = {tb.status_string(s) for s in range(6)}
+    assert len(seen) == 6
+    assert "unknown" in tb.status_string(99)
+
+
+def test_softmax_rejects_bad_arguments_without_a_gpu():
+    L = tb.lib()
+    f = L.turbo_masked_softmax
+    assert f(None, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert f(FAKE, None, 1, 1, 4, 4, 1.0, 7, None) == tb.TURBO_ERR_DTYPE
+    for dims in [(0, 1, 4, 4), (1, 0, 4, 4), (1, 1, 0, 4), (1, 1, 4, 0), (-1, 1, 4, 4), (1, 1, 4, -3)]:
+        assert f(FAKE, None, *dims, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert f(FAKE, None, 1 << 15, 1 << 15, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # 2^32 rows
+    assert f(FAKE + 2, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert f(FAKE + 1, None, 1, 1, 4, 4, 1.0, tb.TURBO_F16, None) == tb.TURBO_ERR_ALIGN
+    assert f(FAKE, FAKE + 0x1002, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    g = L.turbo_masked_softmax_ex
+    assert g(FAKE, FAKE + 0x1000, -4, 0, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert g(FAKE, FAKE + 0x1000, 0, -1, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert g(None, None, 0, 0, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+
+
+def test_layernorm_rejects_bad_arguments_without_a_gpu():
+    L = tb.lib()
+    f = L.turbo_add_bias_layernorm
+    ok = [FAKE, FAKE, FAKE, FAKE, FAKE]
+    assert f(*ok, 4, 8, 1e-5, FAKE, None) != tb.TURBO_ERR_NULL
+    for missing in (0, 3, 4):  # x, gamma, beta are required; residual (1) and bias (2) are optional
+        args = list(ok)
+        args[missing] = None
+        assert f(*args, 4, 8, 1e-5, FAKE, None) == tb.TURBO_ERR_NULL
+    assert f(*ok, 4, 8, 1e-5, None, None) == tb.TURBO_ERR_NULL
+    assert f(*ok, 0, 8, 1e-5, FAKE, None) == tb.TURBO_ERR_SHAPE
+    assert f(*ok, 4, 0, 1e-5, FAKE, None) == tb.TURBO_ERR_SHAPE
+    assert f(*ok, -4, 8, 1e-5, FAKE, None) == tb.TURBO_ERR_SHAPE
+    bad = list(ok)
+    bad[1] = FAKE + 2
+    assert f(*bad, 4, 8, 1e-5, FAKE, None) == tb.TURBO_ERR_ALIGN
+    g = L.turbo_add_bias_layernorm_dt
+    assert g(*ok, 4, 8, 1e-5, FAKE, 5, None) == tb.TURBO_ERR_DTYPE
+    assert g(*ok, 4, 8, 1e-5, FAKE + 1, tb.TURBO_F16, None) == tb.TURBO_ERR_ALIGN
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-GPU failure mode")
+def test_valid_call_without_a_gpu_reports_launch_error_not_a_crash():
+    L = tb.lib()
+    assert L.turbo_masked_softmax(FAKE, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_LAUNCH
+
+
+def test_binding_refuses_host_tensors_and_wrong_dtypes():
+    s = torch.zeros(1, 1, 2, 2)
+    with pytest.raises(ValueError):
+        tb.turbo_masked_softmax(s, None, 1.0)
+    with pytest.raises(TypeError):
+        tb.turbo_masked_softmax(s.double(), None, 1.0)
+
+
+def test_fastdiv_is_exact():
+    L = tb.lib()
+    rng = np.random.default_rng(0)
+    ds = list(range(1, 70)) + [127, 128, 129, 500, 512, 6000, 2 ** 16, 2 ** 16 + 1, 2 ** 31 - 65536]
+    ns = [0, 1, 2, 2 ** 31 - 1, 2 ** 31 - 65536, 2 ** 30, 12345678]
+    for d in ds:
+        for n in ns + [d - 1, d, d + 1, 2 * d - 1, 2 * d, 7 * d + 3]:
+            if 0 <= n < 2 ** 31:
+                assert L.turbo_debug_fastdiv(n, d) == n // d, (n, d)
+    for _ in range(20000):
+        n = int(rng.integers(0, 2 ** 31 - 1))
+        d = int(rng.integers(1, 2 ** 31 - 1)) if rng.random() < 0.5 else int(rng.integers(1, 70000))
+        assert L.turbo_debug_fastdiv(n, d) == n // d, (n, d)
+
+
+def test_plan_families_follow_row_length():
+    P = tb.turbo_describe_plan
+    assert P(0, 192, 16, tb.TURBO_F32) == "wave vec=4 lanes=4 nv=1 rows=8"
+    assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave vec=4 lanes=32 nv=1")
+    assert P(0, 524288, 512, tb.TURBO_F16).startswith("wave vec=8 lanes=64 nv=1")
+    assert P(0, 65536, 4096, tb.TURBO_F32).startswith("wave vec=4 lanes=64 nv=16")
+    assert P(0, 190000, 497, tb.TURBO_F32).startswith("wave vec=1 lanes=64 nv=8")  # odd row length: 4-byte loads
+    assert P(0, 190000, 498, tb.TURBO_F32).startswith("wave vec=2")
+    assert P(1, 4096, 4096, tb.TURBO_F32).startswith("block vec=4 waves=4 nv=4")
+    assert P(0, 100, 8192, tb.TURBO_F32).startswith("block")
+    assert P(0, 100, 40000, tb.TURBO_F32).startswith("stream")
+    assert P(1, 100, 20000, tb.TURBO_F32).startswith("stream")
+    assert P(0, 100, 128, tb.TURBO_F32, aligned16=False).startswith("wave vec=1")
+    tb.turbo_set_override(tb.TURBO_OVR_PATH, tb.PATH_BLOCK)
+    try:
+        assert P(0, 30720, 128, tb.TURBO_F32).startswith("block")
+    finally:
+        tb.turbo_set_override(tb.TURBO_OVR_PATH, -1)
+    assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave")
+    with pytest.raises(tb.TurboError):
+        tb.turbo_set_override(99, 0)

@@ -1,0 +1,317 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.
+
+Bar: |gpu - oracle| <= max(atol, rtol*|oracle|) with (rtol, atol) = (1e-5, 1e-6) for binary32 and
+(3e-3, 1e-6) for binary16 storage, element by element (conftest.assert_parity).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2010_05680_amd import binding as tb
+from paper_2010_05680_amd import workloads as wl
+
+from conftest import assert_parity
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+F32, F16 = np.float32, np.float16
+
+
+def _np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+# ------------------------------------------------------------------ the five configurations
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_softmax_small_configs_full_parity(idx):
+    case = wl.softmax_case(wl.config_spec(idx))
+    got = _np(gu.run_softmax(case))
+    assert_parity(got, gu.oracle_softmax(case), case.scores.dtype, f"softmax cfg{idx}")
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_layernorm_small_configs_full_parity(idx):
+    case = wl.layernorm_case(wl.config_spec(idx))
+    got = _np(gu.run_layernorm(case))
+    assert_parity(got, gu.oracle_layernorm(case), case.x.dtype, f"layernorm cfg{idx}")
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_softmax_full_size_configs_sampled_rows_and_invariants(idx):
+    spec = wl.config_spec(idx)
+    case = wl.softmax_case(spec)
+    print(f"softmax cfg{idx} shape {case.shape} dtype {case.scores.dtype}", flush=True)
+    out = gu.run_softmax(case)
+    B, H, Sq, Sk = case.shape
+    n_rows = B * H * Sq
+    rows = gu.sample_rows(n_rows, 600, seed=idx)
+    got = _np(out.view(n_rows, Sk)[torch.from_numpy(rows).cuda()])
+    assert_parity(got, gu.oracle_softmax_rows(case, rows), case.scores.dtype, f"softmax cfg{idx} sampled rows")
+    # properties that hold at any size, checked on every row
+    sums = out.view(n_rows, Sk).float().sum(-1)
+    tol = 1e-5 if case.scores.dtype == F32 else 2e-3
+    assert torch.isfinite(out).all()
+    assert (sums - 1).abs().max().item() < tol
+    assert out.min().item() >= 0.0 and out.max().item() <= 1.0
+    if case.mask_kind == "key":
+        k = torch.arange(Sk, device="cuda")[None, :]
+        dead = (k >= torch.from_numpy(case.lengths).cuda()[:, None])[:, None, None, :].expand(B, H, Sq, Sk)
+        assert (out[dead] == 0).all()
+    if case.mask_kind == "causal":
+        dead = torch.triu(torch.ones(Sq, Sk, dtype=torch.bool, device="cuda"), 1)
+        assert (out[:, :, dead] == 0).all()
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_layernorm_full_size_configs_sampled_rows_and_invariants(idx):
+    spec = wl.config_spec(idx)
+    case = wl.layernorm_case(spec)
+    print(f"layernorm cfg{idx} shape {case.shape} dtype {case.x.dtype}", flush=True)
+    out = gu.run_layernorm(case)
+    rows = gu.sample_rows(spec.rows, 600, seed=10 + idx)
+    got = _np(out[torch.from_numpy(rows).cuda()])
+    assert_parity(got, gu.oracle_layernorm(case, rows=rows), case.x.dtype, f"layernorm cfg{idx} sampled rows")
+    assert torch.isfinite(out).all()
+    # undo the affine part on the device: mean 0, variance 1 per row
+    g, b = gu.dev(case.gamma).float(), gu.dev(case.beta).float()
+    y = (out.float() - b) / g
+    tol = 1e-4 if case.x.dtype == F32 else 2e-2
+    assert y.mean(-1).abs().max().item() < tol
+    assert (y.var(-1, unbiased=False) - 1).abs().max().item() < 10 * tol
+
+
+# ------------------------------------------------------------------ shape sweeps (full oracle)
+
+TABLE2_GRID = [(1, 10), (1, 100), (1, 500), (20, 10), (20, 100), (20, 500)]
+
+
+@pytest.mark.parametrize("batch,seq", TABLE2_GRID)
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_softmax_table2_grid(batch, seq, dtype):
+    H = 12 if batch * seq < 5000 else 3
+    case = wl.random_softmax_case(1000 + batch * seq, batch, H, seq, seq, dtype=dtype, mask_kind="key")
+    got = _np(gu.run_softmax(case))
+    assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax ({batch},{seq})")
+
+
+@pytest.mark.parametrize("batch,seq", TABLE2_GRID)
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_layernorm_table2_grid(batch, seq, dtype):
+    case = wl.random_layernorm_case(2000 + batch * seq, batch * seq, 768, dtype=dtype)
+    got = _np(gu.run_layernorm(case))
+    assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm ({batch},{seq})")
+
+
+RAGGED_SK = [1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 33, 63, 64, 65, 100, 127, 129, 255, 257, 497, 498, 500, 513, 1000,
+             1023, 1025, 2047, 2052, 4099]
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+@pytest.mark.parametrize("kind", ["none", "key", "causal", "dense"])
+def test_softmax_ragged_row_lengths(dtype, kind):
+    for Sk in RAGGED_SK:
+        Sq = Sk if kind == "causal" and Sk <= 129 else 5
+        if kind == "causal" and Sq != Sk:
+            continue
+        case = wl.random_softmax_case(300 + Sk, 3, 2, Sq, Sk, dtype=dtype, mask_kind=kind)
+        got = _np(gu.run_softmax(case))
+        assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax Sk={Sk} {kind}")
+
+
+RAGGED_HIDDEN = [1, 2, 3, 5, 8, 63, 64, 100, 255, 256, 768, 1000, 1024, 1536, 1540, 2048, 3000, 4096, 4100, 6144]
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_layernorm_ragged_hidden_sizes(dtype):
+    for hidden in RAGGED_HIDDEN:
+        rows = 37 if hidden < 2000 else 9
+        case = wl.random_layernorm_case(400 + hidden, rows, hidden, dtype=dtype, eps=1e-5)
+        if hidden == 1:
+            continue  # a single column has zero variance: the result is eps-dominated, see the dedicated test
+        got = _np(gu.run_layernorm(case))
+        assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm hidden={hidden}")
+
+
+# ------------------------------------------------------------------ every kernel family and vector width
+
+@pytest.mark.parametrize("path", [tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_softmax_forced_families(path, dtype):
+    for Sk, kind in [(16, "key"), (64, "none"), (257, "dense"), (1000, "key"), (2048, "none"), (4096, "key"),
+                     (5001, "none")]:
+        case = wl.random_softmax_case(500 + Sk, 2, 3, 7, Sk, dtype=dtype, mask_kind=kind)
+        with gu.overrides(path=path):
+            got = _np(gu.run_softmax(case))
+        assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax path={path} Sk={Sk}")
+
+
+@pytest.mark.parametrize("path", [tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_layernorm_forced_families(path, dtype):
+    for hidden in (8, 64, 300, 768, 1024, 2048, 4096, 5001):
+        case = wl.random_layernorm_case(600 + hidden, 19, hidden, dtype=dtype, eps=1e-5)
+        with gu.overrides(path=path):
+            got = _np(gu.run_layernorm(case))
+        assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm path={path} hidden={hidden}")
+
+
+@pytest.mark.parametrize("vec_bytes", [2, 4, 8, 16])
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_every_vector_width(vec_bytes, dtype):
+    if vec_bytes < np.dtype(dtype).itemsize:
+        pytest.skip("narrower than one element")
+    with gu.overrides(max_vec_bytes=vec_bytes):
+        for Sk in (64, 512, 1024):
+            case = wl.random_softmax_case(700 + Sk, 2, 2, 33, Sk, dtype=dtype, mask_kind="key")
+            assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), dtype, f"softmax vec={vec_bytes} Sk={Sk}")
+        for hidden in (64, 768, 1024):
+            case = wl.random_layernorm_case(800 + hidden, 45, hidden, dtype=dtype, eps=1e-5)
+            assert_parity(_np(gu.run_layernorm(case)), gu.oracle_layernorm(case), dtype,
+                          f"layernorm vec={vec_bytes} hidden={hidden}")
+
+
+def test_long_rows_block_and_stream_families():
+    for Sk in (8192, 32768, 40000, 70001):
+        case = wl.random_softmax_case(900 + Sk, 1, 2, 3, Sk, mask_kind="key", score_std=5.0)
+        assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), F32, f"softmax Sk={Sk}")
+    for hidden in (8192, 16384, 20000, 65537):
+        case = wl.random_layernorm_case(950 + hidden, 5, hidden, eps=1e-5)
+        assert_parity(_np(gu.run_layernorm(case)), gu.oracle_layernorm(case), F32, f"layernorm hidden={hidden}")
+    case = wl.random_softmax_case(990, 1, 1, 3, 40000, dtype=F16, mask_kind="none")
+    assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), F16, "softmax f16 Sk=40000")
+    case = wl.random_layernorm_case(991, 3, 40000, dtype=F16, eps=1e-5)
+    assert_parity(_np(gu.run_layernorm(case)), gu.oracle_layernorm(case), F16, "layernorm f16 hidden=40000")
+
+
+def test_small_grid_makes_workgroups_loop_over_tiles():
+    with gu.overrides(grid_waves=1):
+        case = wl.softmax_case(wl.config_spec(1))
+        assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), F32, "softmax cfg1, 1 workgroup per CU")
+        lc = wl.layernorm_case(wl.config_spec(1))
+        assert_parity(_np(gu.run_layernorm(lc)), gu.oracle_layernorm(lc), F32, "layernorm cfg1, 1 workgroup per CU")
+        for path in (tb.PATH_BLOCK, tb.PATH_STREAM):
+            with gu.overrides(path=path, grid_waves=1):
+                c = wl.random_softmax_case(77, 2, 2, 700, 300, mask_kind="causal" if False else "key")
+                assert_parity(_np(gu.run_softmax(c)), gu.oracle_softmax(c), F32, f"softmax looped path={path}")
+                l2 = wl.random_layernorm_case(78, 3000, 300, eps=1e-5)
+                assert_parity(_np(gu.run_layernorm(l2)), gu.oracle_layernorm(l2), F32, f"layernorm looped path={path}")
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_softmax_base_entry_point_takes_dense_mask():
+    case = wl.random_softmax_case(31, 3, 4, 9, 40, mask_kind="dense")
+    s, m = gu.dev(case.scores), gu.dev(case.mask)
+    tb.turbo_masked_softmax(s, m, case.scale)
+    torch.cuda.synchronize()
+    assert_parity(_np(s), gu.oracle_softmax(case), F32, "dense mask entry point")
+    case = wl.random_softmax_case(32, 3, 4, 9, 40, mask_kind="none")
+    s = gu.dev(case.scores)
+    tb.turbo_masked_softmax(s, None, case.scale)
+    torch.cuda.synchronize()
+    assert_parity(_np(s), gu.oracle_softmax(case), F32, "NULL mask")
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_unaligned_base_pointers_and_guard_bands(dtype):
+    """Tensors that start 1 element past a 16-byte boundary, inside NaN-filled buffers that must stay untouched."""
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    for Sk in (16, 128, 500, 4096):
+        case = wl.random_softmax_case(40 + Sk, 2, 2, 11, Sk, dtype=dtype, mask_kind="key")
+        n = case.scores.size
+        buf = torch.full((n + 64,), float("nan"), dtype=tdt, device="cuda")
+        view = buf[33:33 + n].view(case.scores.shape)
+        view.copy_(torch.from_numpy(case.scores))
+        mbuf = torch.full((case.mask.size + 9,), float("nan"), dtype=tdt, device="cuda")
+        mview = mbuf[5:5 + case.mask.size].view(case.mask.shape)
+        mview.copy_(torch.from_numpy(case.mask))
+        tb.turbo_masked_softmax_ex(view, mview, case.mask_stride_b, case.mask_stride_q, case.scale)
+        torch.cuda.synchronize()
+        assert_parity(_np(view), gu.oracle_softmax(case), dtype, f"softmax offset view Sk={Sk}")
+        assert torch.isnan(buf[:33]).all() and torch.isnan(buf[33 + n:]).all(), "softmax wrote outside its tensor"
+    for hidden in (64, 768, 1000, 4096):
+        case = wl.random_layernorm_case(60 + hidden, 13, hidden, dtype=dtype, eps=1e-5)
+        n = case.x.size
+        obuf = torch.full((n + 64,), float("nan"), dtype=tdt, device="cuda")
+        out = obuf[31:31 + n].view(case.x.shape)
+        xbuf = torch.zeros(n + 8, dtype=tdt, device="cuda")
+        x = xbuf[3:3 + n].view(case.x.shape)
+        x.copy_(torch.from_numpy(case.x))
+        tb.turbo_add_bias_layernorm_dt(x, gu.dev(case.residual), gu.dev(case.bias), gu.dev(case.gamma),
+                                       gu.dev(case.beta), case.eps, out)
+        torch.cuda.synchronize()
+        assert_parity(_np(out), gu.oracle_layernorm(case), dtype, f"layernorm offset view hidden={hidden}")
+        assert torch.isnan(obuf[:31]).all() and torch.isnan(obuf[31 + n:]).all(), "layernorm wrote outside its tensor"
+
+
+def test_layernorm_optional_inputs_and_aliasing():
+    case = wl.random_layernorm_case(70, 50, 768, eps=1e-5)
+    for residual, bias in [(True, False), (False, True), (False, False)]:
+        got = _np(gu.run_layernorm(case, residual=residual, bias=bias))
+        assert_parity(got, gu.oracle_layernorm(case, residual=residual, bias=bias), F32,
+                      f"layernorm residual={residual} bias={bias}")
+    want = gu.oracle_layernorm(case)
+    x, r = gu.dev(case.x), gu.dev(case.residual)
+    args = (gu.dev(case.bias), gu.dev(case.gamma), gu.dev(case.beta), case.eps)
+    tb.turbo_add_bias_layernorm(x, r, *args, x)  # out aliases x
+    torch.cuda.synchronize()
+    assert_parity(_np(x), want, F32, "layernorm out == x")
+    x = gu.dev(case.x)
+    tb.turbo_add_bias_layernorm(x, r, *args, r)  # out aliases residual
+    torch.cuda.synchronize()
+    assert_parity(_np(r), want, F32, "layernorm out == residual")
+
+
+def test_layernorm_zero_rows_give_beta_and_single_column():
+    case = wl.random_layernorm_case(71, 8, 256, eps=1e-5)
+    case.x[:] = 0
+    case.residual[:] = 0
+    case.bias[:] = 0
+    got = _np(gu.run_layernorm(case))
+    np.testing.assert_array_equal(got, np.broadcast_to(case.beta, got.shape))
+    one = wl.random_layernorm_case(72, 6, 1, eps=1e-5)
+    got = _np(gu.run_layernorm(one))
+    np.testing.assert_allclose(got, np.broadcast_to(one.beta, got.shape), rtol=0, atol=1e-6)
+
+
+def test_softmax_degenerate_rows():
+    # single key: weight 1 whatever the score
+    case = wl.random_softmax_case(80, 2, 3, 4, 1)
+    np.testing.assert_array_equal(_np(gu.run_softmax(case)), np.ones(case.shape, F32))
+    # equal scores: uniform weights
+    case = wl.random_softmax_case(81, 1, 1, 3, 48)
+    case.scores[:] = 2.5
+    np.testing.assert_allclose(_np(gu.run_softmax(case)), 1.0 / 48, rtol=1e-6)
+    # large scores must not overflow
+    case = wl.random_softmax_case(82, 1, 2, 5, 100, score_std=3000.0, scale=1.0)
+    assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), F32, "softmax with |z| in the thousands")
+
+
+def test_softmax_all_keys_masked_row():
+    """Additive semantics: a fully masked row is the softmax of its scores.  binary32 rounds
+    scale*s - 10000 to multiples of 2^-10, so the bar here is the one that rounding allows:
+    |dz| <= 2^-11 per element, i.e. a relative error of about 2*2^-11 on each weight."""
+    case = wl.random_softmax_case(83, 1, 1, 4, 64, mask_kind="key")
+    case.mask[:] = wl.MASK_VALUE
+    got = _np(gu.run_softmax(case))
+    want = gu.oracle_softmax(case)
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got.sum(-1), 1.0, atol=1e-5)
+    np.testing.assert_allclose(got, want, rtol=2.5 * 2.0 ** -10, atol=1e-6)
+
+
+def test_non_default_stream_and_repeat_calls():
+    st = torch.cuda.Stream()
+    case = wl.softmax_case(wl.config_spec(1))
+    lc = wl.layernorm_case(wl.config_spec(1))
+    with torch.cuda.stream(st):
+        got_s = gu.run_softmax(case, stream=st)
+        got_l = gu.run_layernorm(lc, stream=st)
+    st.synchronize()
+    assert_parity(_np(got_s), gu.oracle_softmax(case), F32, "softmax on a side stream")
+    assert_parity(_np(got_l), gu.oracle_layernorm(lc), F32, "layernorm on a side stream")
+    # softmax of a softmax output is a valid input too: the call is repeatable on its own output
+    again = wl.SoftmaxCase(_np(got_s), None, 0, 0, 1.0, "none")
+    assert_parity(_np(gu.run_softmax(again)), gu.oracle_softmax(again), F32, "softmax applied twice")
