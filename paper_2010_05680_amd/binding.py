@@ -15,7 +15,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libturbo_reduce.so")
+# TURBO_REDUCE_LIB selects another build of the same library (e.g. one compiled with different tuning macros).
+LIB_PATH = os.environ.get("TURBO_REDUCE_LIB") or os.path.join(_HERE, "libturbo_reduce.so")
 
 TURBO_OK, TURBO_ERR_NULL, TURBO_ERR_SHAPE, TURBO_ERR_DTYPE, TURBO_ERR_ALIGN, TURBO_ERR_LAUNCH = range(6)
 TURBO_F32, TURBO_F16 = 0, 1

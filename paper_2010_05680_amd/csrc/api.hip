@@ -16,7 +16,6 @@ namespace {
 turbo::Overrides g_ovr;
 
 constexpr int kMaxRows = 0x7FFF0000;  // leaves headroom for tile rounding in 32-bit row indices
-constexpr int kDefaultBlocksPerCu = 8;
 constexpr int kMaxDevices = 64;
 int g_num_cus[kMaxDevices];
 
@@ -60,7 +59,7 @@ int current_num_cus(int* out) {
 turbo::LaunchCfg launch_cfg(int num_cus) {
     turbo::LaunchCfg lc;
     lc.num_cus = num_cus;
-    lc.blocks_per_cu = g_ovr.grid_waves > 0 ? g_ovr.grid_waves : kDefaultBlocksPerCu;
+    lc.waves_per_cu = g_ovr.grid_waves > 0 ? (g_ovr.grid_waves > (1 << 20) ? (1 << 22) : g_ovr.grid_waves * 4) : 0;
     return lc;
 }
 

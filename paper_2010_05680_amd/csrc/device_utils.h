@@ -21,13 +21,57 @@ struct alignas(sizeof(T) * VEC) Pack {
     T v[VEC];
 };
 
-template <typename T, int VEC>
+// Streamed tensors (scores, x, residual, out) are touched exactly once per
+// launch, so their loads and stores carry the non-temporal hint; small operands
+// that every row re-reads (mask rows, bias, gamma, beta) use plain loads.
+#ifndef TURBO_NT_LOADS
+#define TURBO_NT_LOADS 1
+#endif
+#ifndef TURBO_NT_STORES
+#define TURBO_NT_STORES 1
+#endif
+
+// Vector register type for VEC elements of T.  UA ("under-aligned") declares the
+// memory operand aligned to one element only: gfx950 executes 16-byte global
+// loads and stores at any element-aligned address, which keeps rows whose
+// length is not a multiple of the vector width on the wide-access path.
+template <typename T, int VEC, bool UA>
+struct VecType {
+    typedef T reg __attribute__((ext_vector_type(VEC)));
+    typedef reg mem __attribute__((aligned(UA ? sizeof(T) : sizeof(T) * VEC)));
+};
+template <typename T, bool UA>
+struct VecType<T, 1, UA> {
+    typedef T reg;
+    typedef T mem;
+};
+
+// plain load: data with reuse
+template <typename T, int VEC, bool UA = false>
 __device__ __forceinline__ Pack<T, VEC> load_pack(const T* p) {
-    return *reinterpret_cast<const Pack<T, VEC>*>(p);
+    using V = VecType<T, VEC, UA>;
+    typename V::reg v = *reinterpret_cast<const typename V::mem*>(p);
+    return __builtin_bit_cast(Pack<T, VEC>, v);
 }
-template <typename T, int VEC>
-__device__ __forceinline__ void store_pack(T* p, const Pack<T, VEC>& v) {
-    *reinterpret_cast<Pack<T, VEC>*>(p) = v;
+// streaming load / store: data used once
+template <typename T, int VEC, bool UA = false>
+__device__ __forceinline__ Pack<T, VEC> load_stream(const T* p) {
+    using V = VecType<T, VEC, UA>;
+#if TURBO_NT_LOADS
+    typename V::reg v = __builtin_nontemporal_load(reinterpret_cast<const typename V::mem*>(p));
+#else
+    typename V::reg v = *reinterpret_cast<const typename V::mem*>(p);
+#endif
+    return __builtin_bit_cast(Pack<T, VEC>, v);
+}
+template <typename T, int VEC, bool UA = false>
+__device__ __forceinline__ void store_stream(T* p, const Pack<T, VEC>& v) {
+    using V = VecType<T, VEC, UA>;
+#if TURBO_NT_STORES
+    __builtin_nontemporal_store(__builtin_bit_cast(typename V::reg, v), reinterpret_cast<typename V::mem*>(p));
+#else
+    *reinterpret_cast<typename V::mem*>(p) = __builtin_bit_cast(typename V::reg, v);
+#endif
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

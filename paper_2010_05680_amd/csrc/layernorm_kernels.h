@@ -45,11 +45,21 @@ __device__ __forceinline__ void merge_weights_step(float& n, float (&w1)[N], flo
         float na, nb;
         exchange<S>(n, na, nb);
         float nt = na + nb;
-        float inv = nt > 0.f ? 1.0f / nt : 0.f;
+        float inv = nt > 0.f ? fast_rcp(nt) : 0.f;  // counts are small integers; 1 ulp on a weight is harmless
         w1[I] = nb * inv;
         w2[I] = na * nb * inv;
         n = nt;
         merge_weights_step<S * 2, G, I + 1, N>(n, w1, w2);
+    }
+}
+
+// The same weights when every lane holds exactly `cnt` elements: n_a = n_b = cnt * 2^i at step i.
+template <int N>
+__device__ __forceinline__ void merge_weights_full(float cnt, float (&w1)[N], float (&w2)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        w1[i] = 0.5f;
+        w2[i] = cnt * (float)(1 << i) * 0.5f;
     }
 }
 
@@ -70,23 +80,34 @@ __device__ __forceinline__ void merge_stats_step(float (&mean)[R], float (&m2)[R
     }
 }
 
-template <typename T, int VEC>
-__device__ __forceinline__ void load_param(const T* p, int col, bool ok, float (&dst)[VEC], float fill) {
-    if (p != nullptr && ok) {
-        Pack<T, VEC> raw = load_pack<T, VEC>(p + col);
+// One parameter vector widened to float.  `col` must be a readable column (callers
+// clamp columns past the row end to 0; what those lanes hold is never used).
+template <typename T, int VEC, bool UA = false>
+__device__ __forceinline__ void load_param(const T* p, int col, float (&dst)[VEC]) {
+    Pack<T, VEC> raw = load_pack<T, VEC, UA>(p + col);
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) dst[j] = (float)raw.v[j];
+    for (int j = 0; j < VEC; ++j) dst[j] = (float)raw.v[j];
+}
+// The bias may be absent: a null pointer reads as zeros (wave-uniform branch).
+template <typename T, int VEC, bool UA = false>
+__device__ __forceinline__ void load_bias(const T* p, int col, float (&dst)[VEC]) {
+    if (p != nullptr) {
+        load_param<T, VEC, UA>(p, col, dst);
     } else {
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) dst[j] = fill;
+        for (int j = 0; j < VEC; ++j) dst[j] = 0.f;
     }
 }
 
 // ---------------------------------------------------------------------------
 // wave family: G lanes per row, NV vectors per lane, R rows per lane group.
+// The loop is rotated: the loads of a tile are issued first, and the per-kernel
+// set-up (merge weights, parameter vectors) runs while they are in flight.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, bool RES>
+template <typename T, int VEC, int G, int NV, bool RES, int MODE>
 __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
+    constexpr bool UA = MODE == kModeUnder;
+    constexpr bool FULL = MODE == kModeFull;
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
     constexpr int GPW = kWave / G;
     constexpr int kWaves = 4;
@@ -106,48 +127,56 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
     const int grp = lane / G;
     const int hidden = a.hidden;
 
-    float cnt = 0.f;
+    int tile = blockIdx.x;
+    if (tile >= n_tiles) return;
+
+    Pack<T, VEC> xr[R][NV];
+    Pack<T, VEC> rr[R][NV];
+    auto issue_loads = [&](int tl) {
+        const int row_base = tl * TILE_ROWS + wave * (R * GPW) + grp;
 #pragma unroll
-    for (int v = 0; v < NV; ++v)
-        if ((v * G + gl) * VEC < hidden) cnt += (float)VEC;
-    const float inv_cnt = cnt > 0.f ? 1.0f / cnt : 0.f;
-    float w1[STEPS], w2[STEPS];
-    {
-        float n = cnt;
-        merge_weights_step<1, G, 0, STEPS>(n, w1, w2);
-    }
+        for (int r = 0; r < R; ++r) {
+            int row = row_base + r * GPW;
+            int rowc = row < a.n_rows ? row : a.n_rows - 1;  // out-of-range rows recompute the last row, unstored
+            const long long off = (long long)rowc * hidden;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                int colc = FULL ? (v * G + gl) * VEC : vec_start<VEC, UA>((v * G + gl) * VEC, hidden);
+                xr[r][v] = load_stream<T, VEC, UA>(x + off + colc);
+                if constexpr (RES) rr[r][v] = load_stream<T, VEC, UA>(res + off + colc);
+            }
+        }
+    };
+    issue_loads(tile);
 
     float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
     if constexpr (PRELOAD) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * G + gl) * VEC;
-            bool ok = col < hidden;
-            load_param<T, VEC>(bias, col, ok, pb[v], 0.f);
-            load_param<T, VEC>(gamma, col, ok, pg[v], 0.f);
-            load_param<T, VEC>(beta, col, ok, pe[v], 0.f);
+            int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
+            load_bias<T, VEC, UA>(bias, colc, pb[v]);
+            load_param<T, VEC, UA>(gamma, colc, pg[v]);
+            load_param<T, VEC, UA>(beta, colc, pe[v]);
         }
     }
 
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    float cnt = (float)(NV * VEC);
+    float w1[STEPS], w2[STEPS];
+    if constexpr (FULL) {
+        merge_weights_full<STEPS>(cnt, w1, w2);
+    } else {
+        cnt = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+            if ((v * G + gl) * VEC < hidden) cnt += (float)(VEC - vec_overlap<VEC, UA>((v * G + gl) * VEC, hidden));
+        float n = cnt;
+        merge_weights_step<1, G, 0, STEPS>(n, w1, w2);
+    }
+    const float inv_cnt = cnt > 0.f ? fast_rcp(cnt) : 0.f;
+
+    while (true) {
         const int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
-
-        Pack<T, VEC> xr[R][NV];
-        Pack<T, VEC> rr[R][NV];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            int row = row_base + r * GPW;
-            int rowc = row < a.n_rows ? row : a.n_rows - 1;
-            const long long off = (long long)rowc * hidden;
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                int col = (v * G + gl) * VEC;
-                int colc = col < hidden ? col : 0;
-                xr[r][v] = load_pack<T, VEC>(x + off + colc);
-                if constexpr (RES) rr[r][v] = load_pack<T, VEC>(res + off + colc);
-            }
-        }
-
         float t[R][NV][VEC];
         float mean[R], m2[R];
 #pragma unroll
@@ -156,13 +185,14 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int col = (v * G + gl) * VEC;
-                const bool ok = col < hidden;
+                const bool ok = FULL || col < hidden;
+                const int dup = vec_overlap<VEC, UA>(col, hidden);
                 float b[VEC];
                 if constexpr (PRELOAD) {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) b[j] = pb[v][j];
                 } else {
-                    load_param<T, VEC>(bias, col, ok, b, 0.f);
+                    load_bias<T, VEC, UA>(bias, FULL ? col : vec_start<VEC, UA>(col, hidden), b);
                 }
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
@@ -170,24 +200,30 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
                     if constexpr (RES) tv += (float)rr[r][v].v[j];
                     tv = ok ? tv : 0.f;
                     t[r][v][j] = tv;
-                    sum += tv;
+                    sum += (UA && j < dup) ? 0.f : tv;  // overlapped elements are counted by the neighbouring vector
                 }
             }
             const float mu = sum * inv_cnt;
             float q = 0.f;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                const bool ok = (v * G + gl) * VEC < hidden;
+                const bool ok = FULL || (v * G + gl) * VEC < hidden;
+                const int dup = vec_overlap<VEC, UA>((v * G + gl) * VEC, hidden);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     float d = t[r][v][j] - mu;
-                    q += ok ? d * d : 0.f;
+                    q += (ok && !(UA && j < dup)) ? d * d : 0.f;
                 }
             }
             mean[r] = mu;
             m2[r] = q;
         }
         merge_stats_step<1, G, 0, R, STEPS>(mean, m2, w1, w2);
+
+        const int next = tile + (int)gridDim.x;
+        const bool more = next < n_tiles;
+        // the raw registers are dead from here on: refill them for the next tile before storing this one
+        if (more) issue_loads(next);
 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -197,7 +233,8 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int col = (v * G + gl) * VEC;
-                if (row < a.n_rows && col < hidden) {
+                if (row < a.n_rows && (FULL || col < hidden)) {
+                    const int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
                     float g[VEC], be[VEC];
                     if constexpr (PRELOAD) {
 #pragma unroll
@@ -206,16 +243,18 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
                             be[j] = pe[v][j];
                         }
                     } else {
-                        load_param<T, VEC>(gamma, col, true, g, 0.f);
-                        load_param<T, VEC>(beta, col, true, be, 0.f);
+                        load_param<T, VEC, UA>(gamma, colc, g);
+                        load_param<T, VEC, UA>(beta, colc, be);
                     }
                     Pack<T, VEC> o;
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) o.v[j] = (T)fmaf((t[r][v][j] - mean[r]) * rstd, g[j], be[j]);
-                    store_pack<T, VEC>(op + col, o);
+                    store_stream<T, VEC, UA>(op + colc, o);
                 }
             }
         }
+        if (!more) break;
+        tile = next;
     }
 }
 
@@ -251,8 +290,12 @@ __device__ __forceinline__ void layernorm_block_combine(LayerNormLds& lds, int s
 }
 
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
-template <typename T, int VEC, int NV, bool RES>
+// Rotated like the wave family: the next row's loads are issued before this
+// row's barrier and stores.
+template <typename T, int VEC, int NV, bool RES, int MODE>
 __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) {
+    constexpr bool UA = MODE == kModeUnder;
+    constexpr bool FULL = MODE == kModeFull;
     __shared__ LayerNormLds lds;
     constexpr bool PRELOAD = NV * VEC <= kParamPreloadElems;
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
@@ -268,52 +311,65 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     const int hidden = a.hidden;
     const int bd = (int)blockDim.x;
 
-    float cnt = 0.f;
+    int row = blockIdx.x;
+    if (row >= a.n_rows) return;
+
+    Pack<T, VEC> xr[NV];
+    Pack<T, VEC> rr[NV];
+    auto issue_loads = [&](int rw) {
+        const long long off = (long long)rw * hidden;
 #pragma unroll
-    for (int v = 0; v < NV; ++v)
-        if ((v * bd + tid) * VEC < hidden) cnt += (float)VEC;
-    const float inv_cnt = cnt > 0.f ? 1.0f / cnt : 0.f;
-    float w1[6], w2[6];
-    float n_w = cnt;
-    merge_weights_step<1, kWave, 0, 6>(n_w, w1, w2);
+        for (int v = 0; v < NV; ++v) {
+            int colc = FULL ? (v * bd + tid) * VEC : vec_start<VEC, UA>((v * bd + tid) * VEC, hidden);
+            xr[v] = load_stream<T, VEC, UA>(x + off + colc);
+            if constexpr (RES) rr[v] = load_stream<T, VEC, UA>(res + off + colc);
+        }
+    };
+    issue_loads(row);
 
     float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
     if constexpr (PRELOAD) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * bd + tid) * VEC;
-            bool ok = col < hidden;
-            load_param<T, VEC>(bias, col, ok, pb[v], 0.f);
-            load_param<T, VEC>(gamma, col, ok, pg[v], 0.f);
-            load_param<T, VEC>(beta, col, ok, pe[v], 0.f);
+            int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
+            load_bias<T, VEC, UA>(bias, colc, pb[v]);
+            load_param<T, VEC, UA>(gamma, colc, pg[v]);
+            load_param<T, VEC, UA>(beta, colc, pe[v]);
         }
     }
 
-    int slot = 0;
-    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
-        const long long off = (long long)row * hidden;
-        Pack<T, VEC> xr[NV];
-        Pack<T, VEC> rr[NV];
+    float cnt = (float)(NV * VEC);
+    float w1[6], w2[6];
+    float n_w = cnt * (float)kWave;
+    if constexpr (FULL) {
+        merge_weights_full<6>(cnt, w1, w2);
+    } else {
+        cnt = 0.f;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            int col = (v * bd + tid) * VEC;
-            int colc = col < hidden ? col : 0;
-            xr[v] = load_pack<T, VEC>(x + off + colc);
-            if constexpr (RES) rr[v] = load_pack<T, VEC>(res + off + colc);
-        }
+        for (int v = 0; v < NV; ++v)
+            if ((v * bd + tid) * VEC < hidden) cnt += (float)(VEC - vec_overlap<VEC, UA>((v * bd + tid) * VEC, hidden));
+        n_w = cnt;
+        merge_weights_step<1, kWave, 0, 6>(n_w, w1, w2);
+    }
+    const float inv_cnt = cnt > 0.f ? fast_rcp(cnt) : 0.f;
 
+    int slot = 0;
+    while (true) {
+        const long long off = (long long)row * hidden;
         float t[NV][VEC];
         float sum = 0.f;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * bd + tid) * VEC;
-            const bool ok = col < hidden;
+            const bool ok = FULL || col < hidden;
+            const int dup = vec_overlap<VEC, UA>(col, hidden);
             float b[VEC];
             if constexpr (PRELOAD) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) b[j] = pb[v][j];
             } else {
-                load_param<T, VEC>(bias, col, ok, b, 0.f);
+                load_bias<T, VEC, UA>(bias, FULL ? col : vec_start<VEC, UA>(col, hidden), b);
             }
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
@@ -321,28 +377,35 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
                 if constexpr (RES) tv += (float)rr[v].v[j];
                 tv = ok ? tv : 0.f;
                 t[v][j] = tv;
-                sum += tv;
+                sum += (UA && j < dup) ? 0.f : tv;
             }
         }
         float mean[1] = {sum * inv_cnt};
         float m2[1] = {0.f};
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            const bool ok = (v * bd + tid) * VEC < hidden;
+            const bool ok = FULL || (v * bd + tid) * VEC < hidden;
+            const int dup = vec_overlap<VEC, UA>((v * bd + tid) * VEC, hidden);
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
                 float d = t[v][j] - mean[0];
-                m2[0] += ok ? d * d : 0.f;
+                m2[0] += (ok && !(UA && j < dup)) ? d * d : 0.f;
             }
         }
         merge_stats_step<1, kWave, 0, 1, 6>(mean, m2, w1, w2);
+
+        const int next = row + (int)gridDim.x;
+        const bool more = next < a.n_rows;
+        if (more) issue_loads(next);  // the raw registers are dead: refill them before the barrier
+
         layernorm_block_combine(lds, slot, wave, lane, n_waves, n_w, mean[0], m2[0]);
         const float rstd = fast_rsqrt(fmaf(m2[0], a.inv_hidden, a.eps));
 
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * bd + tid) * VEC;
-            if (col < hidden) {
+            if (FULL || col < hidden) {
+                const int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
                 float g[VEC], be[VEC];
                 if constexpr (PRELOAD) {
 #pragma unroll
@@ -351,15 +414,18 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
                         be[j] = pe[v][j];
                     }
                 } else {
-                    load_param<T, VEC>(gamma, col, true, g, 0.f);
-                    load_param<T, VEC>(beta, col, true, be, 0.f);
+                    load_param<T, VEC, UA>(gamma, colc, g);
+                    load_param<T, VEC, UA>(beta, colc, be);
                 }
                 Pack<T, VEC> o;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) o.v[j] = (T)fmaf((t[v][j] - mean[0]) * rstd, g[j], be[j]);
-                store_pack<T, VEC>(out + off + col, o);
+                store_stream<T, VEC, UA>(out + off + colc, o);
             }
         }
+        if (!more) break;
+        row = next;
+        slot ^= 1;
     }
 }
 
@@ -392,11 +458,11 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
         const long long off = (long long)row * hidden;
         float n_run = 0.f, mu_run = 0.f, q_run = 0.f;
         for (long long col = (long long)tid * VEC; col < hidden; col += step) {
-            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);
+            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);  // plain: the row is read again below
             Pack<T, VEC> rr;
             if constexpr (RES) rr = load_pack<T, VEC>(res + off + col);
             float b[VEC];
-            load_param<T, VEC>(bias, (int)col, true, b, 0.f);
+            load_bias<T, VEC>(bias, (int)col, b);
             float t[VEC];
             float s = 0.f;
 #pragma unroll
@@ -423,13 +489,13 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
         const float rstd = fast_rsqrt(fmaf(m2[0], a.inv_hidden, a.eps));
 
         for (long long col = (long long)tid * VEC; col < hidden; col += step) {
-            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);
+            Pack<T, VEC> xr = load_stream<T, VEC>(x + off + col);
             Pack<T, VEC> rr;
-            if constexpr (RES) rr = load_pack<T, VEC>(res + off + col);
+            if constexpr (RES) rr = load_stream<T, VEC>(res + off + col);
             float b[VEC], g[VEC], be[VEC];
-            load_param<T, VEC>(bias, (int)col, true, b, 0.f);
-            load_param<T, VEC>(gamma, (int)col, true, g, 0.f);
-            load_param<T, VEC>(beta, (int)col, true, be, 0.f);
+            load_bias<T, VEC>(bias, (int)col, b);
+            load_param<T, VEC>(gamma, (int)col, g);
+            load_param<T, VEC>(beta, (int)col, be);
             Pack<T, VEC> o;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
@@ -437,7 +503,7 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
                 if constexpr (RES) tv += (float)rr.v[j];
                 o.v[j] = (T)fmaf((tv - mean[0]) * rstd, g[j], be[j]);
             }
-            store_pack<T, VEC>(out + off + col, o);
+            store_stream<T, VEC>(out + off + col, o);
         }
     }
 }
@@ -445,72 +511,90 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
 // ---------------------------------------------------------------------------
 // host-side launch
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, bool RES>
+template <typename T, int VEC, int G, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * 4;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES>), dim3(capped_grid(n_tiles, lc)), dim3(256), 0, s, a,
-                       n_tiles);
+    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>),
+                       dim3(capped_grid(n_tiles, 4, kLayerNormWaveCap, lc)), dim3(256), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, int NV, bool RES>
+template <typename T, int VEC, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    LaunchCfg c = lc;
-    c.blocks_per_cu = lc.blocks_per_cu * 4 / p.waves > 0 ? lc.blocks_per_cu * 4 / p.waves : 1;
-    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES>), dim3(capped_grid(a.n_rows, c)), dim3(64 * p.waves), 0,
-                       s, a);
+    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>),
+                       dim3(capped_grid(a.n_rows, p.waves, kLayerNormBlockCap, lc)), dim3(64 * p.waves), 0, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, bool RES>
+template <typename T, int VEC, bool RES, int MODE>
 hipError_t launch_layernorm_vr(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     if (p.path == kPathWave) {
         if (p.lanes < 64) {
-            switch (p.lanes) {
-                case 4: return launch_layernorm_wave<T, VEC, 4, 1, RES>(a, lc, s);
-                case 8: return launch_layernorm_wave<T, VEC, 8, 1, RES>(a, lc, s);
-                case 16: return launch_layernorm_wave<T, VEC, 16, 1, RES>(a, lc, s);
-                case 32: return launch_layernorm_wave<T, VEC, 32, 1, RES>(a, lc, s);
+            if (p.nv == 1) {
+                switch (p.lanes) {
+                    case 4: return launch_layernorm_wave<T, VEC, 4, 1, RES, MODE>(a, lc, s);
+                    case 8: return launch_layernorm_wave<T, VEC, 8, 1, RES, MODE>(a, lc, s);
+                    case 16: return launch_layernorm_wave<T, VEC, 16, 1, RES, MODE>(a, lc, s);
+                    case 32: return launch_layernorm_wave<T, VEC, 32, 1, RES, MODE>(a, lc, s);
+                }
+            } else if constexpr (MODE == kModeFull) {  // narrower groups with several vectors only when they tile the row
+                if (p.lanes == 32 && p.nv == 3) return launch_layernorm_wave<T, VEC, 32, 3, RES, MODE>(a, lc, s);
+                if constexpr (5 * VEC <= kLayerNormLimits.wave_max_epl)
+                    if (p.lanes == 32 && p.nv == 5) return launch_layernorm_wave<T, VEC, 32, 5, RES, MODE>(a, lc, s);
+                if (p.lanes == 16 && p.nv == 3) return launch_layernorm_wave<T, VEC, 16, 3, RES, MODE>(a, lc, s);
             }
             return hipErrorInvalidValue;
         }
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 1, RES>(a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 2, RES>(a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 3, RES>(a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 4, RES>(a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 6, RES>(a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 8, RES>(a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 12, RES>(a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 16, RES>(a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 1, RES, MODE>(a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 2, RES, MODE>(a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 3, RES, MODE>(a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 4, RES, MODE>(a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 5, RES, MODE>(a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 6, RES, MODE>(a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 8, RES, MODE>(a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 12, RES, MODE>(a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kLayerNormLimits.wave_max_epl) return launch_layernorm_wave<T, VEC, 64, 16, RES, MODE>(a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
     if (p.path == kPathBlock) {
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kLayerNormLimits.block_max_epl || 1 == 1) return launch_layernorm_block<T, VEC, 1, RES>(p, a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kLayerNormLimits.block_max_epl || 2 == 1) return launch_layernorm_block<T, VEC, 2, RES>(p, a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kLayerNormLimits.block_max_epl || 3 == 1) return launch_layernorm_block<T, VEC, 3, RES>(p, a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kLayerNormLimits.block_max_epl || 4 == 1) return launch_layernorm_block<T, VEC, 4, RES>(p, a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kLayerNormLimits.block_max_epl || 6 == 1) return launch_layernorm_block<T, VEC, 6, RES>(p, a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kLayerNormLimits.block_max_epl || 8 == 1) return launch_layernorm_block<T, VEC, 8, RES>(p, a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kLayerNormLimits.block_max_epl || 12 == 1) return launch_layernorm_block<T, VEC, 12, RES>(p, a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kLayerNormLimits.block_max_epl || 16 == 1) return launch_layernorm_block<T, VEC, 16, RES>(p, a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kLayerNormLimits.block_max_epl || 1 == 1) return launch_layernorm_block<T, VEC, 1, RES, MODE>(p, a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kLayerNormLimits.block_max_epl || 2 == 1) return launch_layernorm_block<T, VEC, 2, RES, MODE>(p, a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kLayerNormLimits.block_max_epl || 3 == 1) return launch_layernorm_block<T, VEC, 3, RES, MODE>(p, a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kLayerNormLimits.block_max_epl || 4 == 1) return launch_layernorm_block<T, VEC, 4, RES, MODE>(p, a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kLayerNormLimits.block_max_epl) return launch_layernorm_block<T, VEC, 5, RES, MODE>(p, a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kLayerNormLimits.block_max_epl || 6 == 1) return launch_layernorm_block<T, VEC, 6, RES, MODE>(p, a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kLayerNormLimits.block_max_epl || 8 == 1) return launch_layernorm_block<T, VEC, 8, RES, MODE>(p, a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kLayerNormLimits.block_max_epl || 12 == 1) return launch_layernorm_block<T, VEC, 12, RES, MODE>(p, a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kLayerNormLimits.block_max_epl || 16 == 1) return launch_layernorm_block<T, VEC, 16, RES, MODE>(p, a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
-    LaunchCfg c = lc;
-    c.blocks_per_cu = 2;
-    hipLaunchKernelGGL((layernorm_stream_kernel<T, VEC, RES>), dim3(capped_grid(a.n_rows, c)), dim3(kStreamThreads), 0,
-                       s, a);
+    hipLaunchKernelGGL((layernorm_stream_kernel<T, VEC, RES>),
+                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool RES, bool UA_OK>
+hipError_t launch_layernorm_m(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    switch (row_mode(p)) {
+        case kModeFull: return launch_layernorm_vr<T, VEC, RES, kModeFull>(p, a, lc, s);
+        case kModeRagged: return launch_layernorm_vr<T, VEC, RES, kModeRagged>(p, a, lc, s);
+        case kModeUnder:
+            if constexpr (UA_OK) return launch_layernorm_vr<T, VEC, RES, kModeUnder>(p, a, lc, s);
+            break;
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename T, int VEC, bool UA_OK = false>
 hipError_t launch_layernorm_v(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    return a.residual ? launch_layernorm_vr<T, VEC, true>(p, a, lc, s) : launch_layernorm_vr<T, VEC, false>(p, a, lc, s);
+    return a.residual ? launch_layernorm_m<T, VEC, true, UA_OK>(p, a, lc, s)
+                      : launch_layernorm_m<T, VEC, false, UA_OK>(p, a, lc, s);
 }
 
 hipError_t launch_layernorm_f32(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s);

@@ -16,6 +16,12 @@ namespace turbo {
 
 enum PathKind { kPathWave = 0, kPathBlock = 1, kPathStream = 2 };
 
+// How a kernel treats the end of a row.
+//   kModeFull   : the lanes tile the row exactly; no bounds checks at all.
+//   kModeRagged : aligned vectors, lanes past the row end are masked.
+//   kModeUnder  : element-aligned wide vectors; the last one overlaps its neighbour.
+enum RowMode { kModeFull = 0, kModeRagged = 1, kModeUnder = 2 };
+
 constexpr int kMaxNV = 16;                 // most vectors a lane keeps in registers
 constexpr int kWaveMaxVecs = 64 * kMaxNV;  // longest row (in vectors) a single wavefront may own
 constexpr int kBlockMaxWaves = 16;
@@ -25,15 +31,38 @@ constexpr int kStreamThreads = 1024;
 struct OpLimits {
     int target_elems;    // wave: rows in flight are chosen so a lane holds about this many values
     int wave_max_epl;    // wave: most elements of one row per lane
-    int block_pref_epl;  // block: grow the workgroup until a lane holds at most this many
-    int block_max_epl;   // block: most elements per lane at 16 wavefronts (1024 threads, 128 VGPRs)
+    int block_pref_nv;   // block: grow the workgroup until a lane holds at most this many vectors
+    int block_max_epl;   // block: most elements per lane (1024 threads leave 128 VGPRs each)
+    int block_from_vecs; // rows of at least this many vectors go to the block family even if a wavefront could hold them
 };
-constexpr OpLimits kSoftmaxLimits{32, 64, 16, 32};
-constexpr OpLimits kLayerNormLimits{16, 24, 16, 16};
+#ifndef TURBO_SM_TARGET_ELEMS
+#define TURBO_SM_TARGET_ELEMS 32
+#endif
+#ifndef TURBO_LN_TARGET_ELEMS
+#define TURBO_LN_TARGET_ELEMS 16
+#endif
+#ifndef TURBO_SM_BLOCK_PREF_NV
+#define TURBO_SM_BLOCK_PREF_NV 2
+#endif
+#ifndef TURBO_LN_BLOCK_PREF_NV
+#define TURBO_LN_BLOCK_PREF_NV 4
+#endif
+#ifndef TURBO_SM_BLOCK_FROM_VECS
+#define TURBO_SM_BLOCK_FROM_VECS 256
+#endif
+#ifndef TURBO_LN_BLOCK_FROM_VECS
+#define TURBO_LN_BLOCK_FROM_VECS 100000
+#endif
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_VECS};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_VECS};
 
 struct Plan {
     int path;    // PathKind
     int vec;     // elements per load/store
+    int under_aligned;  // 1: accesses are `vec` wide but only element-aligned; the row's last vector is
+                        //    shifted back to end at the row end and overlaps its neighbour
+    int full;           // 1: lanes * nv * vec (times waves for the block family) equals the row length exactly,
+                        //    so no lane needs a bounds check
     int lanes;   // wave: lanes per row (G)
     int nv;      // vectors per lane
     int rows;    // wave: rows a lane group works on concurrently (R)
@@ -47,10 +76,17 @@ struct Overrides {
 };
 
 inline int round_up_nv(int nv) {
-    static const int supported[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    static const int supported[] = {1, 2, 3, 4, 5, 6, 8, 12, 16};
     for (int s : supported)
         if (nv <= s) return s;
     return -1;
+}
+
+// (lanes per row, vectors per lane) pairs the wave family is compiled for.
+inline bool wave_shape_supported(int lanes, int nv) {
+    if (lanes == 64) return round_up_nv(nv) == nv;
+    if (nv == 1) return lanes == 4 || lanes == 8 || lanes == 16 || lanes == 32;
+    return (lanes == 32 && (nv == 3 || nv == 5)) || (lanes == 16 && nv == 3);
 }
 
 inline int pow2_ceil(int x) {
@@ -76,9 +112,16 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     int vec_bytes = 16;
     if (ovr.max_vec_bytes >= elem_size && ovr.max_vec_bytes < 16) vec_bytes = ovr.max_vec_bytes;
     int vec = vec_bytes / elem_size;
-    while (vec > 1 && (row_len % vec != 0 || align_elems % vec != 0)) vec >>= 1;
+    p.under_aligned = 0;
+    if (row_len % vec != 0 || align_elems % vec != 0) {
+        if (row_len >= vec && vec > 1 && ovr.max_vec_bytes < 0) {
+            p.under_aligned = 1;  // keep the full width; hardware handles element-aligned wide accesses
+        } else {
+            while (vec > 1 && (row_len % vec != 0 || align_elems % vec != 0)) vec >>= 1;
+        }
+    }
     p.vec = vec;
-    const long long nvec = row_len / vec;
+    const long long nvec = (row_len + vec - 1) / vec;
 
     // wave family: feasible when one wavefront's registers hold the row
     bool wave_ok = false;
@@ -93,6 +136,19 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
             wave_g = g;
             wave_nv = nv;
         }
+        // Prefer a lane group that tiles the row exactly (no masked lanes, constant merge weights),
+        // e.g. 96 vectors = 32 lanes x 3 rather than 64 lanes x 2 with a quarter of them idle.
+        if (!p.under_aligned && (long long)g * nv * vec != row_len) {
+            for (int gg = 64; gg >= 4; gg >>= 1) {
+                if (nvec % gg != 0) continue;
+                int q = (int)(nvec / gg);
+                if (q > kMaxNV || !wave_shape_supported(gg, q) || q * vec > lim.wave_max_epl) continue;
+                wave_ok = true;
+                wave_g = gg;
+                wave_nv = q;
+                break;
+            }
+        }
     }
     // block family: smallest workgroup that meets the preferred budget, else 16 wavefronts
     bool block_ok = false;
@@ -101,8 +157,8 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         long long per_lane = (nvec + 64 * w - 1) / (64 * w);
         if (per_lane > kMaxNV) continue;
         int nv = round_up_nv((int)per_lane);
-        int budget = w < kBlockMaxWaves ? lim.block_pref_epl : lim.block_max_epl;
-        if (nv * vec <= budget || (nv == 1 && w == 2)) {
+        const bool fits = nv * vec <= lim.block_max_epl || nv == 1;
+        if (fits && (nv <= lim.block_pref_nv || w == kBlockMaxWaves)) {
             block_ok = true;
             block_w = w;
             block_nv = nv;
@@ -113,13 +169,19 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     int path;
     if (wave_ok) {
         // Long rows with few of them: a workgroup per row exposes more parallelism.
-        path = (block_ok && nvec >= 512 && n_rows < 4096) ? kPathBlock : kPathWave;
+        path = (block_ok && (nvec >= lim.block_from_vecs || (nvec >= 512 && n_rows < 4096))) ? kPathBlock : kPathWave;
     } else {
         path = block_ok ? kPathBlock : kPathStream;
     }
     if (ovr.path == kPathWave && wave_ok) path = kPathWave;
     if (ovr.path == kPathBlock && block_ok) path = kPathBlock;
     if (ovr.path == kPathStream) path = kPathStream;
+    if (path == kPathStream && p.under_aligned) {
+        // the two-sweep kernels only take aligned vectors: narrow the access instead
+        p.under_aligned = 0;
+        while (vec > 1 && (row_len % vec != 0 || align_elems % vec != 0)) vec >>= 1;
+        p.vec = vec;
+    }
     p.path = path;
 
     if (path == kPathWave) {
@@ -138,15 +200,21 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         p.nv = 1;
         p.rows = 1;
     }
+    p.full = 0;
+    if (!p.under_aligned && path == kPathWave) p.full = (long long)p.lanes * p.nv * vec == row_len;
+    if (!p.under_aligned && path == kPathBlock) p.full = 64ll * p.waves * p.nv * vec == row_len;
     return p;
 }
 
+inline int row_mode(const Plan& p) { return p.under_aligned ? kModeUnder : p.full ? kModeFull : kModeRagged; }
+
 inline void describe_plan(const Plan& p, char* buf, int n) {
     static const char* names[] = {"wave", "block", "stream"};
+    const char* ua = p.under_aligned ? "u" : p.full ? "f" : "";
     if (p.path == kPathWave)
-        std::snprintf(buf, n, "%s vec=%d lanes=%d nv=%d rows=%d", names[p.path], p.vec, p.lanes, p.nv, p.rows);
+        std::snprintf(buf, n, "%s vec=%d%s lanes=%d nv=%d rows=%d", names[p.path], p.vec, ua, p.lanes, p.nv, p.rows);
     else
-        std::snprintf(buf, n, "%s vec=%d waves=%d nv=%d", names[p.path], p.vec, p.waves, p.nv);
+        std::snprintf(buf, n, "%s vec=%d%s waves=%d nv=%d", names[p.path], p.vec, ua, p.waves, p.nv);
 }
 
 }  // namespace turbo

@@ -5,7 +5,7 @@ namespace turbo {
 
 hipError_t launch_softmax_f32(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     switch (p.vec) {
-        case 4: return launch_softmax_v<float, 4>(p, a, lc, s);
+        case 4: return launch_softmax_v<float, 4, true>(p, a, lc, s);
         case 2: return launch_softmax_v<float, 2>(p, a, lc, s);
         case 1: return launch_softmax_v<float, 1>(p, a, lc, s);
     }

@@ -33,8 +33,17 @@ struct SoftmaxArgs {
 
 struct LaunchCfg {
     int num_cus;
-    int blocks_per_cu;  // cap on the grid, in workgroups per compute unit
+    int waves_per_cu;  // caller's cap on resident wavefronts per compute unit used to size the grid; <= 0: family default
 };
+
+// Default grid caps, in wavefronts per compute unit (0 = one tile or row per workgroup, no cap).
+// Softmax has no per-workgroup set-up, and a grid of short-lived workgroups streams best.
+// LayerNorm workgroups keep bias/gamma/beta in registers, so they are persistent and loop.
+constexpr int kSoftmaxWaveCap = 0;
+constexpr int kSoftmaxBlockCap = 0;
+constexpr int kLayerNormWaveCap = 64;
+constexpr int kLayerNormBlockCap = 32;
+constexpr int kStreamCap = 32;
 
 constexpr int rows_in_flight_c(int nv, int vec, int target) {
     int r = target / (nv * vec);
@@ -52,13 +61,33 @@ __device__ __forceinline__ const T* mask_row_ptr(const SoftmaxArgs& a, int row) 
     }
 }
 
+// Where the vector that nominally starts at column `col` is read and written.
+// Aligned mode: at `col` (row lengths are multiples of VEC).  Under-aligned mode:
+// the row's last vector is shifted back so that it ends exactly at the row end;
+// it then overlaps its left neighbour by vec_overlap() elements, which are
+// excluded from the row sums and written twice with the same value.  A vector
+// past the row end reads column 0 and is never stored.
+template <int VEC, bool UA>
+__device__ __forceinline__ int vec_start(int col, int row_len) {
+    if (col >= row_len) return 0;
+    if constexpr (UA) return col + VEC <= row_len ? col : row_len - VEC;
+    return col;
+}
+template <int VEC, bool UA>
+__device__ __forceinline__ int vec_overlap(int col, int row_len) {
+    if constexpr (UA) return (col < row_len && col + VEC > row_len) ? col + VEC - row_len : 0;
+    return 0;
+}
+
 // ---------------------------------------------------------------------------
 // wave family: G lanes per row, NV vectors per lane, R rows per lane group.
 // Lane `gl` of a group holds vectors gl, gl+G, gl+2G, ... of its row, so one load
 // instruction of a wavefront covers 64/G consecutive rows in 16*G-byte pieces.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, bool MASK>
+template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
 __global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
+    constexpr bool UA = MODE == kModeUnder;
+    constexpr bool FULL = MODE == kModeFull;
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int GPW = kWave / G;  // lane groups per wavefront
     constexpr int kWaves = 4;
@@ -85,10 +114,9 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_
             const T* mp = mask_row_ptr<T, MASK>(a, rowc);
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                int col = (v * G + gl) * VEC;
-                int colc = col < Sk ? col : 0;
-                raw[r][v] = load_pack<T, VEC>(rp + colc);
-                if constexpr (MASK) mraw[r][v] = load_pack<T, VEC>(mp + colc);
+                int colc = FULL ? (v * G + gl) * VEC : vec_start<VEC, UA>((v * G + gl) * VEC, Sk);
+                raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
+                if constexpr (MASK) mraw[r][v] = load_pack<T, VEC, UA>(mp + colc);
             }
         }
 
@@ -99,7 +127,7 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_
             m[r] = -INFINITY;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                const bool ok = (v * G + gl) * VEC < Sk;
+                const bool ok = FULL || (v * G + gl) * VEC < Sk;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     float s = (float)raw[r][v].v[j];
@@ -122,13 +150,15 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_
             const float shift = -m[r] * kLog2e;
             l[r] = 0.f;
 #pragma unroll
-            for (int v = 0; v < NV; ++v)
+            for (int v = 0; v < NV; ++v) {
+                const int dup = vec_overlap<VEC, UA>((v * G + gl) * VEC, Sk);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     float e = fast_exp2(fmaf(z[r][v][j], kLog2e, shift));
                     z[r][v][j] = e;
-                    l[r] += e;
+                    l[r] += (UA && j < dup) ? 0.f : e;  // overlapped elements belong to the neighbouring vector
                 }
+            }
         }
         group_allreduce<G, R>(l, SumOp{});
 
@@ -140,11 +170,11 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int col = (v * G + gl) * VEC;
-                if (row < a.n_rows && col < Sk) {
+                if (row < a.n_rows && (FULL || col < Sk)) {
                     Pack<T, VEC> o;
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
-                    store_pack<T, VEC>(rp + col, o);
+                    store_stream<T, VEC, UA>(rp + (FULL ? col : vec_start<VEC, UA>(col, Sk)), o);
                 }
             }
         }
@@ -178,8 +208,10 @@ __device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot
 }
 
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
-template <typename T, int VEC, int NV, bool MASK>
+template <typename T, int VEC, int NV, bool MASK, int MODE>
 __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
+    constexpr bool UA = MODE == kModeUnder;
+    constexpr bool FULL = MODE == kModeFull;
     __shared__ SoftmaxLds lds;
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int tid = threadIdx.x;
@@ -198,17 +230,16 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
         Pack<T, VEC> mraw[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            int col = (v * (int)blockDim.x + tid) * VEC;
-            int colc = col < Sk ? col : 0;
-            raw[v] = load_pack<T, VEC>(rp + colc);
-            if constexpr (MASK) mraw[v] = load_pack<T, VEC>(mp + colc);
+            int colc = FULL ? (v * (int)blockDim.x + tid) * VEC : vec_start<VEC, UA>((v * (int)blockDim.x + tid) * VEC, Sk);
+            raw[v] = load_stream<T, VEC, UA>(rp + colc);
+            if constexpr (MASK) mraw[v] = load_pack<T, VEC, UA>(mp + colc);
         }
 
         float z[NV][VEC];
         float m[1] = {-INFINITY};
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            const bool ok = (v * (int)blockDim.x + tid) * VEC < Sk;
+            const bool ok = FULL || (v * (int)blockDim.x + tid) * VEC < Sk;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
                 float s = (float)raw[v].v[j];
@@ -228,13 +259,15 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 
         float l[1] = {0.f};
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
+        for (int v = 0; v < NV; ++v) {
+            const int dup = vec_overlap<VEC, UA>((v * (int)blockDim.x + tid) * VEC, Sk);
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
                 float e = fast_exp2(fmaf(z[v][j], kLog2e, shift));
                 z[v][j] = e;
-                l[0] += e;
+                l[0] += (UA && j < dup) ? 0.f : e;
             }
+        }
         group_allreduce<kWave, 1>(l, SumOp{});
 
         const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
@@ -242,11 +275,11 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * (int)blockDim.x + tid) * VEC;
-            if (col < Sk) {
+            if (FULL || col < Sk) {
                 Pack<T, VEC> o;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[v][j] * f);
-                store_pack<T, VEC>(rp + col, o);
+                store_stream<T, VEC, UA>(rp + (FULL ? col : vec_start<VEC, UA>(col, Sk)), o);
             }
         }
     }
@@ -274,7 +307,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
 
         float m_run = -INFINITY, l_run = 0.f;
         for (long long col = (long long)tid * VEC; col < Sk; col += step) {
-            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);
+            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);  // plain: the row is read again below
             Pack<T, VEC> mraw;
             if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
             float z[VEC];
@@ -309,7 +342,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
         // exp2((z - m_w) log2e) * f == exp(z - M)/L; a wavefront with no element stores nothing
         const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
         for (long long col = (long long)tid * VEC; col < Sk; col += step) {
-            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);
+            Pack<T, VEC> raw = load_stream<T, VEC>(rp + col);
             Pack<T, VEC> mraw;
             if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
             Pack<T, VEC> o;
@@ -323,7 +356,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
                     zz = s * scale;
                 o.v[j] = (T)(fast_exp2(fmaf(zz, kLog2e, shift)) * f);
             }
-            store_pack<T, VEC>(rp + col, o);
+            store_stream<T, VEC>(rp + col, o);
         }
     }
 }
@@ -331,78 +364,102 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
 // ---------------------------------------------------------------------------
 // host-side launch
 // ---------------------------------------------------------------------------
-inline int capped_grid(long long work_items, const LaunchCfg& lc) {
-    long long cap = (long long)lc.num_cus * lc.blocks_per_cu;
-    long long g = work_items < cap ? work_items : cap;
+inline int capped_grid(long long work_items, int waves_per_block, int default_cap, const LaunchCfg& lc) {
+    const int cap_waves = lc.waves_per_cu > 0 ? lc.waves_per_cu : default_cap;
+    long long g = work_items;
+    if (cap_waves > 0) {
+        long long cap = (long long)lc.num_cus * cap_waves / waves_per_block;
+        if (cap < lc.num_cus) cap = lc.num_cus;
+        if (g > cap) g = cap;
+    }
+    if (g > 0x7FFFFFFF) g = 0x7FFFFFFF;
     return (int)(g < 1 ? 1 : g);
 }
 
-template <typename T, int VEC, int G, int NV, bool MASK>
+template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
 hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * 4;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK>), dim3(capped_grid(n_tiles, lc)), dim3(256), 0, s, a,
-                       n_tiles);
+    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK, MODE>), dim3(capped_grid(n_tiles, 4, kSoftmaxWaveCap, lc)),
+                       dim3(256), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, int NV, bool MASK>
+template <typename T, int VEC, int NV, bool MASK, int MODE>
 hipError_t launch_softmax_block(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    LaunchCfg c = lc;
-    c.blocks_per_cu = lc.blocks_per_cu * 4 / p.waves > 0 ? lc.blocks_per_cu * 4 / p.waves : 1;
-    hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MASK>), dim3(capped_grid(a.n_rows, c)), dim3(64 * p.waves), 0,
-                       s, a);
+    hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MASK, MODE>),
+                       dim3(capped_grid(a.n_rows, p.waves, kSoftmaxBlockCap, lc)), dim3(64 * p.waves), 0, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, bool MASK>
+template <typename T, int VEC, bool MASK, int MODE>
 hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     if (p.path == kPathWave) {
         if (p.lanes < 64) {
-            switch (p.lanes) {
-                case 4: return launch_softmax_wave<T, VEC, 4, 1, MASK>(a, lc, s);
-                case 8: return launch_softmax_wave<T, VEC, 8, 1, MASK>(a, lc, s);
-                case 16: return launch_softmax_wave<T, VEC, 16, 1, MASK>(a, lc, s);
-                case 32: return launch_softmax_wave<T, VEC, 32, 1, MASK>(a, lc, s);
+            if (p.nv == 1) {
+                switch (p.lanes) {
+                    case 4: return launch_softmax_wave<T, VEC, 4, 1, MASK, MODE>(a, lc, s);
+                    case 8: return launch_softmax_wave<T, VEC, 8, 1, MASK, MODE>(a, lc, s);
+                    case 16: return launch_softmax_wave<T, VEC, 16, 1, MASK, MODE>(a, lc, s);
+                    case 32: return launch_softmax_wave<T, VEC, 32, 1, MASK, MODE>(a, lc, s);
+                }
+            } else if constexpr (MODE == kModeFull) {  // narrower groups with several vectors only when they tile the row
+                if (p.lanes == 32 && p.nv == 3) return launch_softmax_wave<T, VEC, 32, 3, MASK, MODE>(a, lc, s);
+                if constexpr (5 * VEC <= kSoftmaxLimits.wave_max_epl)
+                    if (p.lanes == 32 && p.nv == 5) return launch_softmax_wave<T, VEC, 32, 5, MASK, MODE>(a, lc, s);
+                if (p.lanes == 16 && p.nv == 3) return launch_softmax_wave<T, VEC, 16, 3, MASK, MODE>(a, lc, s);
             }
             return hipErrorInvalidValue;
         }
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 1, MASK>(a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 2, MASK>(a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 3, MASK>(a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 4, MASK>(a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 6, MASK>(a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 8, MASK>(a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 12, MASK>(a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 16, MASK>(a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 1, MASK, MODE>(a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 2, MASK, MODE>(a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 3, MASK, MODE>(a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 4, MASK, MODE>(a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 5, MASK, MODE>(a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 6, MASK, MODE>(a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 8, MASK, MODE>(a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 12, MASK, MODE>(a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 16, MASK, MODE>(a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
     if (p.path == kPathBlock) {
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MASK>(p, a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MASK>(p, a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MASK>(p, a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MASK>(p, a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MASK>(p, a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MASK>(p, a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MASK>(p, a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MASK>(p, a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MASK, MODE>(p, a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MASK, MODE>(p, a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MASK, MODE>(p, a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MASK, MODE>(p, a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.block_max_epl) return launch_softmax_block<T, VEC, 5, MASK, MODE>(p, a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MASK, MODE>(p, a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MASK, MODE>(p, a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MASK, MODE>(p, a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MASK, MODE>(p, a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
-    LaunchCfg c = lc;
-    c.blocks_per_cu = 2;
-    hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MASK>), dim3(capped_grid(a.n_rows, c)), dim3(kStreamThreads), 0, s,
-                       a);
+    hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MASK>),
+                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VEC>
+// UA_OK: the under-aligned flavour exists only for the widest vector of each element type.
+template <typename T, int VEC, bool MASK, bool UA_OK>
+hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    switch (row_mode(p)) {
+        case kModeFull: return launch_softmax_vm<T, VEC, MASK, kModeFull>(p, a, lc, s);
+        case kModeRagged: return launch_softmax_vm<T, VEC, MASK, kModeRagged>(p, a, lc, s);
+        case kModeUnder:
+            if constexpr (UA_OK) return launch_softmax_vm<T, VEC, MASK, kModeUnder>(p, a, lc, s);
+            break;
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename T, int VEC, bool UA_OK = false>
 hipError_t launch_softmax_v(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    return a.mask ? launch_softmax_vm<T, VEC, true>(p, a, lc, s) : launch_softmax_vm<T, VEC, false>(p, a, lc, s);
+    return a.mask ? launch_softmax_m<T, VEC, true, UA_OK>(p, a, lc, s) : launch_softmax_m<T, VEC, false, UA_OK>(p, a, lc, s);
 }
 
 // Defined once per element type in softmax_f32.hip / softmax_f16.hip.

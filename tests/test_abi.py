@@ -106,17 +106,29 @@ def test_fastdiv_is_exact():
 
 def test_plan_families_follow_row_length():
     P = tb.turbo_describe_plan
-    assert P(0, 192, 16, tb.TURBO_F32) == "wave vec=4 lanes=4 nv=1 rows=8"
-    assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave vec=4 lanes=32 nv=1")
-    assert P(0, 524288, 512, tb.TURBO_F16).startswith("wave vec=8 lanes=64 nv=1")
-    assert P(0, 65536, 4096, tb.TURBO_F32).startswith("wave vec=4 lanes=64 nv=16")
-    assert P(0, 190000, 497, tb.TURBO_F32).startswith("wave vec=1 lanes=64 nv=8")  # odd row length: 4-byte loads
-    assert P(0, 190000, 498, tb.TURBO_F32).startswith("wave vec=2")
-    assert P(1, 4096, 4096, tb.TURBO_F32).startswith("block vec=4 waves=4 nv=4")
+    # "f": the lanes tile the row exactly, no bounds checks
+    assert P(0, 192, 16, tb.TURBO_F32) == "wave vec=4f lanes=4 nv=1 rows=8"
+    assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave vec=4f lanes=32 nv=1")
+    assert P(0, 524288, 512, tb.TURBO_F16).startswith("wave vec=8f lanes=64 nv=1")
+    assert P(0, 65536, 4096, tb.TURBO_F32).startswith("block vec=4f waves=8 nv=2")  # long rows: a workgroup per row
+    assert P(0, 1000, 100, tb.TURBO_F32).startswith("wave vec=4 lanes=32 nv=1")  # 25 vectors on 32 lanes: masked tail
+    # odd row length: still 16-byte accesses, element-aligned ("u"), last vector overlaps its neighbour
+    assert P(0, 190000, 497, tb.TURBO_F32).startswith("wave vec=4u lanes=64 nv=2")
+    assert P(0, 190000, 498, tb.TURBO_F32).startswith("wave vec=4u")
+    assert P(0, 10, 3, tb.TURBO_F32).startswith("wave vec=1 ")  # shorter than one vector: narrow accesses
+    assert P(1, 4096, 4096, tb.TURBO_F32).startswith("block vec=4f waves=4 nv=4")
+    assert P(1, 2560, 768, tb.TURBO_F32).startswith("wave vec=4f lanes=64 nv=3")
     assert P(0, 100, 8192, tb.TURBO_F32).startswith("block")
     assert P(0, 100, 40000, tb.TURBO_F32).startswith("stream")
     assert P(1, 100, 20000, tb.TURBO_F32).startswith("stream")
-    assert P(0, 100, 128, tb.TURBO_F32, aligned16=False).startswith("wave vec=1")
+    assert P(0, 100, 128, tb.TURBO_F32, aligned16=False).startswith("wave vec=4u lanes=32")
+    assert P(0, 100, 40001, tb.TURBO_F32).startswith("stream vec=1 ")  # two-sweep kernels narrow the access instead
+    tb.turbo_set_override(tb.TURBO_OVR_MAX_VEC_BYTES, 16)
+    try:  # an explicit width cap also selects the aligned narrow kernels
+        assert P(0, 190000, 497, tb.TURBO_F32).startswith("wave vec=1 lanes=64 nv=8")
+        assert P(0, 190000, 498, tb.TURBO_F32).startswith("wave vec=2")
+    finally:
+        tb.turbo_set_override(tb.TURBO_OVR_MAX_VEC_BYTES, -1)
     tb.turbo_set_override(tb.TURBO_OVR_PATH, tb.PATH_BLOCK)
     try:
         assert P(0, 30720, 128, tb.TURBO_F32).startswith("block")

@@ -108,30 +108,37 @@ RAGGED_SK = [1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 33, 63, 64, 65, 100, 127, 129,
              1023, 1025, 2047, 2052, 4099]
 
 
+@pytest.mark.parametrize("wide", [True, False], ids=["element-aligned-wide", "aligned-narrow"])
 @pytest.mark.parametrize("dtype", [F32, F16])
 @pytest.mark.parametrize("kind", ["none", "key", "causal", "dense"])
-def test_softmax_ragged_row_lengths(dtype, kind):
-    for Sk in RAGGED_SK:
-        Sq = Sk if kind == "causal" and Sk <= 129 else 5
-        if kind == "causal" and Sq != Sk:
-            continue
-        case = wl.random_softmax_case(300 + Sk, 3, 2, Sq, Sk, dtype=dtype, mask_kind=kind)
-        got = _np(gu.run_softmax(case))
-        assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax Sk={Sk} {kind}")
+def test_softmax_ragged_row_lengths(dtype, kind, wide):
+    """Row lengths that are not multiples of the vector width: by default 16-byte accesses at element
+    alignment with an overlapping last vector; with a width cap, the aligned 2/4/8-byte kernels."""
+    with gu.overrides(max_vec_bytes=-1 if wide else 16):
+        for Sk in RAGGED_SK:
+            Sq = Sk if kind == "causal" and Sk <= 129 else 5
+            if kind == "causal" and Sq != Sk:
+                continue
+            case = wl.random_softmax_case(300 + Sk, 3, 2, Sq, Sk, dtype=dtype, mask_kind=kind)
+            got = _np(gu.run_softmax(case))
+            assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax Sk={Sk} {kind}")
 
 
-RAGGED_HIDDEN = [1, 2, 3, 5, 8, 63, 64, 100, 255, 256, 768, 1000, 1024, 1536, 1540, 2048, 3000, 4096, 4100, 6144]
+RAGGED_HIDDEN = [1, 2, 3, 5, 8, 9, 63, 64, 100, 255, 256, 257, 768, 771, 1000, 1024, 1027, 1536, 1540, 2048, 3001, 4096, 4100, 4101,
+                 6144, 6147]
 
 
+@pytest.mark.parametrize("wide", [True, False], ids=["element-aligned-wide", "aligned-narrow"])
 @pytest.mark.parametrize("dtype", [F32, F16])
-def test_layernorm_ragged_hidden_sizes(dtype):
-    for hidden in RAGGED_HIDDEN:
-        rows = 37 if hidden < 2000 else 9
-        case = wl.random_layernorm_case(400 + hidden, rows, hidden, dtype=dtype, eps=1e-5)
-        if hidden == 1:
-            continue  # a single column has zero variance: the result is eps-dominated, see the dedicated test
-        got = _np(gu.run_layernorm(case))
-        assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm hidden={hidden}")
+def test_layernorm_ragged_hidden_sizes(dtype, wide):
+    with gu.overrides(max_vec_bytes=-1 if wide else 16):
+        for hidden in RAGGED_HIDDEN:
+            rows = 37 if hidden < 2000 else 9
+            case = wl.random_layernorm_case(400 + hidden, rows, hidden, dtype=dtype, eps=1e-5)
+            if hidden == 1:
+                continue  # a single column has zero variance: the result is eps-dominated, see the dedicated test
+            got = _np(gu.run_layernorm(case))
+            assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm hidden={hidden}")
 
 
 # ------------------------------------------------------------------ every kernel family and vector width
@@ -139,8 +146,8 @@ def test_layernorm_ragged_hidden_sizes(dtype):
 @pytest.mark.parametrize("path", [tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
 @pytest.mark.parametrize("dtype", [F32, F16])
 def test_softmax_forced_families(path, dtype):
-    for Sk, kind in [(16, "key"), (64, "none"), (257, "dense"), (1000, "key"), (2048, "none"), (4096, "key"),
-                     (5001, "none")]:
+    for Sk, kind in [(16, "key"), (64, "none"), (257, "dense"), (1000, "key"), (1001, "key"), (2048, "none"),
+                     (4096, "key"), (5001, "none")]:
         case = wl.random_softmax_case(500 + Sk, 2, 3, 7, Sk, dtype=dtype, mask_kind=kind)
         with gu.overrides(path=path):
             got = _np(gu.run_softmax(case))
@@ -150,7 +157,7 @@ def test_softmax_forced_families(path, dtype):
 @pytest.mark.parametrize("path", [tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
 @pytest.mark.parametrize("dtype", [F32, F16])
 def test_layernorm_forced_families(path, dtype):
-    for hidden in (8, 64, 300, 768, 1024, 2048, 4096, 5001):
+    for hidden in (8, 64, 300, 301, 768, 1024, 2048, 2049, 4096, 5001):
         case = wl.random_layernorm_case(600 + hidden, 19, hidden, dtype=dtype, eps=1e-5)
         with gu.overrides(path=path):
             got = _np(gu.run_layernorm(case))
