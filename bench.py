@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--cpu-baseline", type=int, default=1, help="time the CPU oracle on a bounded sample (0/1)")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
     ap.add_argument("--kernel-iters", type=int, default=100, help="launches per kernel timing")
+    ap.add_argument("--traffic-probe", type=int, default=0,
+                    help="run only: one plain copy of a known size, then N cold launches of each kernel of --config; "
+                         "meant to run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
     return ap.parse_args()
 
 
@@ -143,6 +146,28 @@ def time_launches(torch, stream, fn, iters, period, launch):
     return start.elapsed_time(stop) / n, n, mode
 
 
+COPY_PROBE_BYTES = 256 << 20
+
+
+def traffic_probe(torch, ks, stream, n):
+    """Calibration copy + n launches of each kernel, eager, on one stream, for HBM-byte counters.
+
+    The copy is torch's elementwise copy kernel over COPY_PROBE_BYTES (reads that many bytes, writes that
+    many): the ratio counter/known-bytes it yields scales the counters of the two kernels."""
+    src = torch.randn(COPY_PROBE_BYTES // 4, device="cuda")
+    dst = torch.empty_like(src)
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            dst.copy_(src)
+        for i in range(n):
+            ks.softmax(i, stream)
+        for i in range(n):
+            ks.layernorm(i, stream)
+        stream.synchronize()
+    print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": COPY_PROBE_BYTES,
+                      "softmax_bytes": ks.softmax_bytes, "layernorm_bytes": ks.layernorm_bytes, "launches": n}))
+
+
 def cpu_baseline(spec, wl, budget_s=10.0):
     """The oracle as it stands, on the headline workload, on the host cores of this machine."""
     from oracle import turbo_oracle as orc
@@ -207,6 +232,9 @@ def main():
 
     spec = wl.config_spec(args.config)
     ks = KernelSets(spec, torch, tb, wl)
+    if args.traffic_probe:
+        traffic_probe(torch, ks, stream, args.traffic_probe)
+        return
     period = max(ks.n_sm_sets, ks.n_ln_sets)
     step_bytes = ks.softmax_bytes + ks.layernorm_bytes
 

@@ -19,7 +19,10 @@
 
 namespace turbo {
 
-constexpr int kParamPreloadElems = 16;     // keep bias/gamma/beta in registers up to this many columns per lane
+#ifndef TURBO_LN_PRELOAD_ELEMS
+#define TURBO_LN_PRELOAD_ELEMS 16
+#endif
+constexpr int kParamPreloadElems = TURBO_LN_PRELOAD_ELEMS;     // keep bias/gamma/beta in registers up to this many columns per lane
 
 struct LayerNormArgs {
     const void* x;
@@ -100,9 +103,11 @@ __device__ __forceinline__ void load_bias(const T* p, int col, float (&dst)[VEC]
 }
 
 // ---------------------------------------------------------------------------
-// wave family: G lanes per row, NV vectors per lane, R rows per lane group.
-// The loop is rotated: the loads of a tile are issued first, and the per-kernel
+// wave family: G lanes per row, NV vectors per lane, R rows per lane group, one
+// tile of rows per workgroup.  The loads of the tile are issued first; the
 // set-up (merge weights, parameter vectors) runs while they are in flight.
+// Measured on MI355X, short-lived workgroups stream better here than
+// persistent ones that keep the parameters across tiles.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC, int G, int NV, bool RES, int MODE>
 __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
     const int grp = lane / G;
     const int hidden = a.hidden;
 
-    int tile = blockIdx.x;
+    const int tile = blockIdx.x;
     if (tile >= n_tiles) return;
 
     Pack<T, VEC> xr[R][NV];
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
     }
     const float inv_cnt = cnt > 0.f ? fast_rcp(cnt) : 0.f;
 
-    while (true) {
+    {
         const int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
         float t[R][NV][VEC];
         float mean[R], m2[R];
@@ -220,11 +225,6 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
         }
         merge_stats_step<1, G, 0, R, STEPS>(mean, m2, w1, w2);
 
-        const int next = tile + (int)gridDim.x;
-        const bool more = next < n_tiles;
-        // the raw registers are dead from here on: refill them for the next tile before storing this one
-        if (more) issue_loads(next);
-
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             int row = row_base + r * GPW;
@@ -253,8 +253,6 @@ __global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, in
                 }
             }
         }
-        if (!more) break;
-        tile = next;
     }
 }
 
@@ -516,8 +514,7 @@ hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hi
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * 4;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>),
-                       dim3(capped_grid(n_tiles, 4, kLayerNormWaveCap, lc)), dim3(256), 0, s, a, n_tiles);
+    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>), dim3(n_tiles), dim3(256), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 

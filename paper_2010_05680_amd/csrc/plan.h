@@ -33,7 +33,7 @@ struct OpLimits {
     int wave_max_epl;    // wave: most elements of one row per lane
     int block_pref_nv;   // block: grow the workgroup until a lane holds at most this many vectors
     int block_max_epl;   // block: most elements per lane (1024 threads leave 128 VGPRs each)
-    int block_from_vecs; // rows of at least this many vectors go to the block family even if a wavefront could hold them
+    int block_from_bytes;  // rows of at least this many bytes go to the block family even if a wavefront could hold them
 };
 #ifndef TURBO_SM_TARGET_ELEMS
 #define TURBO_SM_TARGET_ELEMS 32
@@ -45,16 +45,16 @@ struct OpLimits {
 #define TURBO_SM_BLOCK_PREF_NV 2
 #endif
 #ifndef TURBO_LN_BLOCK_PREF_NV
-#define TURBO_LN_BLOCK_PREF_NV 4
+#define TURBO_LN_BLOCK_PREF_NV 2
 #endif
-#ifndef TURBO_SM_BLOCK_FROM_VECS
-#define TURBO_SM_BLOCK_FROM_VECS 256
+#ifndef TURBO_SM_BLOCK_FROM_BYTES
+#define TURBO_SM_BLOCK_FROM_BYTES 4096
 #endif
-#ifndef TURBO_LN_BLOCK_FROM_VECS
-#define TURBO_LN_BLOCK_FROM_VECS 100000
+#ifndef TURBO_LN_BLOCK_FROM_BYTES
+#define TURBO_LN_BLOCK_FROM_BYTES (1 << 30)
 #endif
-constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_VECS};
-constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_VECS};
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES};
 
 struct Plan {
     int path;    // PathKind
@@ -150,26 +150,32 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
             }
         }
     }
-    // block family: smallest workgroup that meets the preferred budget, else 16 wavefronts
+    // block family: the smallest workgroup of at most 8 wavefronts whose lanes hold at most the preferred
+    // number of vectors; failing that, up to twice as many vectors with up to 16 wavefronts; failing that,
+    // 16 wavefronts with whatever still fits the register budget.
     bool block_ok = false;
     int block_w = 0, block_nv = 0;
-    for (int w = 2; w <= kBlockMaxWaves; w *= 2) {
-        long long per_lane = (nvec + 64 * w - 1) / (64 * w);
-        if (per_lane > kMaxNV) continue;
-        int nv = round_up_nv((int)per_lane);
-        const bool fits = nv * vec <= lim.block_max_epl || nv == 1;
-        if (fits && (nv <= lim.block_pref_nv || w == kBlockMaxWaves)) {
-            block_ok = true;
-            block_w = w;
-            block_nv = nv;
-            break;
+    for (int pass = 0; pass < 3 && !block_ok; ++pass) {
+        const int max_w = pass == 0 ? 8 : kBlockMaxWaves;
+        const int max_nv = pass == 0 ? lim.block_pref_nv : pass == 1 ? 2 * lim.block_pref_nv : kMaxNV;
+        for (int w = 2; w <= max_w; w *= 2) {
+            long long per_lane = (nvec + 64 * w - 1) / (64 * w);
+            if (per_lane > kMaxNV) continue;
+            int nv = round_up_nv((int)per_lane);
+            const bool fits = nv * vec <= lim.block_max_epl || nv == 1;
+            if (fits && nv <= max_nv) {
+                block_ok = true;
+                block_w = w;
+                block_nv = nv;
+                break;
+            }
         }
     }
 
     int path;
     if (wave_ok) {
         // Long rows with few of them: a workgroup per row exposes more parallelism.
-        path = (block_ok && (nvec >= lim.block_from_vecs || (nvec >= 512 && n_rows < 4096))) ? kPathBlock : kPathWave;
+        path = (block_ok && ((long long)row_len * elem_size >= lim.block_from_bytes || (nvec >= 512 && n_rows < 4096))) ? kPathBlock : kPathWave;
     } else {
         path = block_ok ? kPathBlock : kPathStream;
     }

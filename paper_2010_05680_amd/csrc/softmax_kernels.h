@@ -38,10 +38,10 @@ struct LaunchCfg {
 
 // Default grid caps, in wavefronts per compute unit (0 = one tile or row per workgroup, no cap).
 // Softmax has no per-workgroup set-up, and a grid of short-lived workgroups streams best.
-// LayerNorm workgroups keep bias/gamma/beta in registers, so they are persistent and loop.
+// LayerNorm's workgroup-per-row family keeps bias/gamma/beta in registers, so it is persistent and loops;
+// its lane-group family launches one tile of rows per workgroup.
 constexpr int kSoftmaxWaveCap = 0;
 constexpr int kSoftmaxBlockCap = 0;
-constexpr int kLayerNormWaveCap = 64;
 constexpr int kLayerNormBlockCap = 32;
 constexpr int kStreamCap = 32;
 

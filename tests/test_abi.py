@@ -115,8 +115,10 @@ def test_plan_families_follow_row_length():
     # odd row length: still 16-byte accesses, element-aligned ("u"), last vector overlaps its neighbour
     assert P(0, 190000, 497, tb.TURBO_F32).startswith("wave vec=4u lanes=64 nv=2")
     assert P(0, 190000, 498, tb.TURBO_F32).startswith("wave vec=4u")
+    assert P(1, 1000, 771, tb.TURBO_F32).startswith("wave vec=4u lanes=64 nv=4")
+    assert P(0, 1000, 100, tb.TURBO_F16).startswith("wave vec=8u lanes=16 nv=1")
     assert P(0, 10, 3, tb.TURBO_F32).startswith("wave vec=1 ")  # shorter than one vector: narrow accesses
-    assert P(1, 4096, 4096, tb.TURBO_F32).startswith("block vec=4f waves=4 nv=4")
+    assert P(1, 4096, 4096, tb.TURBO_F32).startswith("block vec=4f waves=8 nv=2")
     assert P(1, 2560, 768, tb.TURBO_F32).startswith("wave vec=4f lanes=64 nv=3")
     assert P(0, 100, 8192, tb.TURBO_F32).startswith("block")
     assert P(0, 100, 40000, tb.TURBO_F32).startswith("stream")
