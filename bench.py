@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a plain copy of known size); written from the counter runs described beside it.
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic_pmc_configs1-4.json")
 COLD_BYTES = 640 << 20       # rotate over at least this many bytes of operands
 MAX_SETS = 24
 
@@ -284,8 +287,18 @@ def main():
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
         "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(ms_dom * 1e3, 3), "launches": n_dom,
-        "timing": f"hip events on the launch stream, {dom_mode} launches, cold (rotating {dom_period} buffer sets)",
+        "timing": f"one HIP event pair around {n_dom} back-to-back {dom_mode} launches on the launch stream, cold "
+                  f"(rotating {dom_period} buffer sets)",
     }
+
+    try:
+        with open(TRAFFIC_JSON) as fh:
+            entry = json.load(fh).get(f"cfg{spec.index}_{dom}")
+        if entry and entry.get("algorithmic_bytes") == dom_bytes:
+            roofline["traffic"] = entry["traffic_bytes"]
+            roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/"
+    except (OSError, ValueError):
+        pass
 
     # ---- every config, both kernels, cold and warm ----
     per_config = []
