@@ -1,0 +1,53 @@
+"""The pins must notice a plausible mistake anywhere in the oracle.
+
+Each case plants one mistake in a COPY of oracle/turbo_oracle.c (a dropped term, a wrong sign or index, a
+transposed operand), compiles it on the CPU, and runs the pin suite against it in a subprocess: the suite has to fail.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "turbo_oracle.c")
+
+MUTATIONS = [
+    ("mask_is_scaled", "double z = scale * s[k] + (a ? a[k] : 0.0);", "double z = scale * (s[k] + (a ? a[k] : 0.0));"),
+    ("mask_subtracted", "double z = scale * s[k] + (a ? a[k] : 0.0);", "double z = scale * s[k] - (a ? a[k] : 0.0);"),
+    ("scale_dropped", "double z = scale * s[k] + (a ? a[k] : 0.0);", "double z = s[k] + (a ? a[k] : 0.0);"),
+    ("mask_strides_swapped", "mask + b * mask_stride_b + q * mask_stride_q", "mask + q * mask_stride_b + b * mask_stride_q"),
+    ("query_index_wrong", "long long q = row % Sq;", "long long q = row % H;"),
+    ("batch_index_wrong", "long long b = row / ((long long)H * Sq);", "long long b = row / Sq;"),
+    ("no_max_shift", "y[k] = exp(y[k] - m);", "y[k] = exp(y[k]);"),
+    ("max_starts_at_zero", "double m = -INFINITY;", "double m = 0.0;"),
+    ("not_normalised", "for (int k = 0; k < Sk; ++k) y[k] /= l;", ""),
+    ("sample_variance", "double var = ss / hidden;", "double var = ss / (hidden - 1);"),
+    ("eps_outside_sqrt", "double inv = 1.0 / sqrt(var + eps);", "double inv = 1.0 / (sqrt(var) + eps);"),
+    ("bias_dropped", "double t = xr[j] + (bias ? bias[j] : 0.0) + (rr ? rr[j] : 0.0);", "double t = xr[j] + (rr ? rr[j] : 0.0);"),
+    ("residual_dropped", "double t = xr[j] + (bias ? bias[j] : 0.0) + (rr ? rr[j] : 0.0);", "double t = xr[j] + (bias ? bias[j] : 0.0);"),
+    ("residual_subtracted", "(bias ? bias[j] : 0.0) + (rr ? rr[j] : 0.0);", "(bias ? bias[j] : 0.0) - (rr ? rr[j] : 0.0);"),
+    ("gamma_beta_swapped", "(o[j] - mu) * inv * gamma[j] + beta[j];", "(o[j] - mu) * inv * beta[j] + gamma[j];"),
+    ("mean_not_removed_in_variance", "double d = o[j] - mu;\n            ss += d * d;", "double d = o[j];\n            ss += d * d;"),
+    ("mean_not_removed_in_output", "o[j] = (o[j] - mu) * inv * gamma[j] + beta[j];", "o[j] = o[j] * inv * gamma[j] + beta[j];"),
+    ("residual_row_stride_wrong", "residual ? residual + r * hidden : NULL;", "residual ? residual + r : NULL;"),
+    ("eq1_second_form_wrong", "return s2 / n - mu * mu;", "return s2 / n - mu;"),
+    ("welford_update_wrong", "m2 += d * (x[i] - mean);", "m2 += d * d;"),
+    ("chan_cross_term_dropped", "*m2 = m2_a + m2_b + d * d * (na * nb / nt);", "*m2 = m2_a + m2_b;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_pins_catch_planted_mistake(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site for {name} not found exactly once"
+    mutated = tmp_path / "mutant.c"
+    mutated.write_text(text.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-o", str(lib),
+                           str(mutated), "-lm"])
+    env = dict(os.environ, TURBO_ORACLE_LIB=str(lib))
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                          "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True)
+    assert res.returncode != 0, f"the pins did not notice the planted mistake '{name}'"
+    assert "failed" in res.stdout or "error" in res.stdout.lower()
