@@ -156,3 +156,60 @@ void oracle_welford_merge(double na, double mean_a, double m2_a, double nb, doub
     *mean = mean_a + d * (nb / nt);
     *m2 = m2_a + m2_b + d * d * (na * nb / nt);
 }
+
+/* ---- element-wise fused kernels (Section 4.1.1: "fused activation functions and fused transpose
+ * operations are composed of element-wise operations") ------------------------------------------------
+ * The paper names the two kinds but prints no formula or layout.  Readings taken here:
+ *   - the activation is GELU, the feed-forward activation of the BERT family the paper evaluates:
+ *     gelu(t) = t * Phi(t), Phi the standard normal distribution function (approximate = 0), or its
+ *     usual tanh form 0.5 t (1 + tanh(sqrt(2/pi) (t + 0.044715 t^3))) (approximate = 1);
+ *   - the fused transposes are the head split after the Q/K/V projection (bias added on the way) and
+ *     the head merge after attention.
+ */
+
+/* out[r][j] = gelu(x[r][j] + bias[j]); bias may be NULL. */
+void oracle_add_bias_gelu(const double *x, const double *bias, long long rows, int hidden, int approximate,
+                          double *out)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long long r = 0; r < rows; ++r) {
+        for (int j = 0; j < hidden; ++j) {
+            double t = x[r * hidden + j] + (bias ? bias[j] : 0.0);
+            double y;
+            if (approximate) {
+                double u = 0.7978845608028654 * (t + 0.044715 * t * t * t); /* sqrt(2/pi) */
+                y = 0.5 * t * (1.0 + tanh(u));
+            } else {
+                y = t * 0.5 * erfc(-t * 0.7071067811865476); /* Phi(t) = erfc(-t/sqrt 2)/2 */
+            }
+            out[r * hidden + j] = y;
+        }
+    }
+}
+
+/* Head split with bias: x is [B][S][n_split][H][D] (the output of one fused projection, n_split = 3 for
+ * Q, K, V together, 1 for a single projection), bias is [n_split][H][D] or NULL, out is
+ * [n_split][B][H][S][D]:  out[k][b][h][s][d] = x[b][s][k][h][d] + bias[k][h][d]. */
+void oracle_add_bias_split_heads(const double *x, const double *bias, int B, int S, int n_split, int H, int D,
+                                 double *out)
+{
+    for (int k = 0; k < n_split; ++k)
+        for (int b = 0; b < B; ++b)
+            for (int h = 0; h < H; ++h)
+                for (int s = 0; s < S; ++s)
+                    for (int d = 0; d < D; ++d) {
+                        long long src = ((((long long)b * S + s) * n_split + k) * H + h) * D + d;
+                        long long dst = ((((long long)k * B + b) * H + h) * S + s) * D + d;
+                        out[dst] = x[src] + (bias ? bias[((long long)k * H + h) * D + d] : 0.0);
+                    }
+}
+
+/* Head merge: x is [B][H][S][D], out is [B][S][H][D]:  out[b][s][h][d] = x[b][h][s][d]. */
+void oracle_merge_heads(const double *x, int B, int H, int S, int D, double *out)
+{
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int s = 0; s < S; ++s)
+                for (int d = 0; d < D; ++d)
+                    out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];
+}

@@ -54,6 +54,12 @@ def _load():
             f.restype = ctypes.c_double
         lib.oracle_welford_merge.argtypes = [ctypes.c_double] * 6 + [_dp] * 3
         lib.oracle_welford_merge.restype = None
+        lib.oracle_add_bias_gelu.argtypes = [_dp, _dp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, _dp]
+        lib.oracle_add_bias_gelu.restype = None
+        lib.oracle_add_bias_split_heads.argtypes = [_dp, _dp] + [ctypes.c_int] * 5 + [_dp]
+        lib.oracle_add_bias_split_heads.restype = None
+        lib.oracle_merge_heads.argtypes = [_dp] + [ctypes.c_int] * 4 + [_dp]
+        lib.oracle_merge_heads.restype = None
         _lib = lib
     return _lib
 
@@ -138,3 +144,45 @@ def welford_merge(a, b):
     _load().oracle_welford_merge(*(float(v) for v in a), *(float(v) for v in b), ctypes.byref(n),
                                  ctypes.byref(mean), ctypes.byref(m2))
     return n.value, mean.value, m2.value
+
+
+def add_bias_gelu(x, bias, approximate: bool = False) -> np.ndarray:
+    """gelu(x + bias) over [rows, hidden]; erf form by default, tanh form with approximate=True; float64 result."""
+    xx = _f64(x)
+    if xx.ndim != 2:
+        raise ValueError("x must be [rows, hidden]")
+    rows, hidden = xx.shape
+    bb = None if bias is None else _f64(bias)
+    if bb is not None and bb.shape != (hidden,):
+        raise ValueError("bias shape")
+    out = np.empty_like(xx)
+    if xx.size:
+        _load().oracle_add_bias_gelu(_ptr(xx), _ptr(bb), rows, hidden, int(bool(approximate)), _ptr(out))
+    return out
+
+
+def add_bias_split_heads(x, bias) -> np.ndarray:
+    """[B,S,n_split,H,D] (+ bias [n_split,H,D]) -> [n_split,B,H,S,D]; float64 result."""
+    xx = _f64(x)
+    if xx.ndim != 5:
+        raise ValueError("x must be [B,S,n_split,H,D]")
+    B, S, K, H, D = xx.shape
+    bb = None if bias is None else _f64(bias)
+    if bb is not None and bb.shape != (K, H, D):
+        raise ValueError("bias must be [n_split,H,D]")
+    out = np.empty((K, B, H, S, D), dtype=np.float64)
+    if xx.size:
+        _load().oracle_add_bias_split_heads(_ptr(xx), _ptr(bb), B, S, K, H, D, _ptr(out))
+    return out
+
+
+def merge_heads(x) -> np.ndarray:
+    """[B,H,S,D] -> [B,S,H,D]; float64 result."""
+    xx = _f64(x)
+    if xx.ndim != 4:
+        raise ValueError("x must be [B,H,S,D]")
+    B, H, S, D = xx.shape
+    out = np.empty((B, S, H, D), dtype=np.float64)
+    if xx.size:
+        _load().oracle_merge_heads(_ptr(xx), B, H, S, D, _ptr(out))
+    return out

@@ -34,6 +34,16 @@ MUTATIONS = [
     ("eq1_second_form_wrong", "return s2 / n - mu * mu;", "return s2 / n - mu;"),
     ("welford_update_wrong", "m2 += d * (x[i] - mean);", "m2 += d * d;"),
     ("chan_cross_term_dropped", "*m2 = m2_a + m2_b + d * d * (na * nb / nt);", "*m2 = m2_a + m2_b;"),
+    ("gelu_erfc_sign", "y = t * 0.5 * erfc(-t * 0.7071067811865476);", "y = t * 0.5 * erfc(t * 0.7071067811865476);"),
+    ("gelu_missing_half", "y = t * 0.5 * erfc(-t * 0.7071067811865476);", "y = t * erfc(-t * 0.7071067811865476);"),
+    ("gelu_tanh_cubic_constant", "0.044715 * t * t * t", "0.44715 * t * t * t"),
+    ("gelu_tanh_square_not_cube", "0.044715 * t * t * t", "0.044715 * t * t"),
+    ("gelu_bias_dropped", "double t = x[r * hidden + j] + (bias ? bias[j] : 0.0);", "double t = x[r * hidden + j];"),
+    ("split_source_order", "((((long long)b * S + s) * n_split + k) * H + h) * D + d;", "((((long long)b * S + s) * H + h) * n_split + k) * D + d;"),
+    ("split_dest_heads_and_sequence_swapped", "((((long long)k * B + b) * H + h) * S + s) * D + d;", "((((long long)k * B + b) * S + s) * H + h) * D + d;"),
+    ("split_bias_ignores_split_index", "bias[((long long)k * H + h) * D + d]", "bias[((long long)h) * D + d]"),
+    ("merge_is_a_copy", "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];",
+     "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * S + s) * H + h) * D + d];"),
 ]
 
 
@@ -47,7 +57,8 @@ def test_pins_catch_planted_mistake(tmp_path, name, old, new):
     subprocess.check_call(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-o", str(lib),
                            str(mutated), "-lm"])
     env = dict(os.environ, TURBO_ORACLE_LIB=str(lib))
-    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                          os.path.join(ROOT, "tests", "test_oracle_pins_elementwise.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True)
     assert res.returncode != 0, f"the pins did not notice the planted mistake '{name}'"
     assert "failed" in res.stdout or "error" in res.stdout.lower()
