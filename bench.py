@@ -171,6 +171,58 @@ def traffic_probe(torch, ks, stream, n):
                       "softmax_bytes": ks.softmax_bytes, "layernorm_bytes": ks.layernorm_bytes, "launches": n}))
 
 
+def elementwise_table(torch, tb, stream, launch, iters):
+    """Cold timings of the element-wise fused kernels on the shapes that go with configs 1 and 4:
+    feed-forward activation [B*S, 4*hidden], Q/K/V head split [B,S,3,H,64] and head merge [B,H,S,64]."""
+    rows = []
+    for label, tdt, es, B, S, H, D in (("config 1 model (BERT-base, f32)", torch.float32, 4, 20, 128, 12, 64),
+                                       ("config 4 model (GPT-2-medium, f16)", torch.float16, 2, 64, 512, 16, 64)):
+        hidden = H * D
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(20100568 + es)
+
+        def sets(shape, per_set_bytes):
+            n = int(max(2, min(MAX_SETS, -(-COLD_BYTES // per_set_bytes))))
+            return [torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(tdt) for _ in range(n)], n
+
+        entry = {"model": label}
+        # bias + GELU on [B*S, 4*hidden]
+        n_el = B * S * 4 * hidden
+        xs, n = sets((B * S, 4 * hidden), 2 * es * n_el)
+        outs = [torch.empty_like(x) for x in xs]
+        bias = torch.randn((4 * hidden,), generator=gen, device="cuda").to(tdt)
+        for approx, name in ((False, "add_bias_gelu_erf"), (True, "add_bias_gelu_tanh")):
+            ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_gelu(xs[i % n], bias, approx, outs[i % n],
+                                                                                  stream=stream), iters, n, launch)
+            nbytes = 2 * es * n_el + es * 4 * hidden
+            entry[name] = {"shape": [B * S, 4 * hidden], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
+                           "cold_GBs": round(nbytes / ms / 1e6, 1), "cold_frac_of_8TBs": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del xs, outs
+        # Q/K/V head split with bias, then head merge
+        n_el = B * S * 3 * hidden
+        xs, n = sets((B, S, 3, H, D), 2 * es * n_el)
+        outs = [torch.empty((3, B, H, S, D), device="cuda", dtype=tdt) for _ in xs]
+        b3 = torch.randn((3, H, D), generator=gen, device="cuda").to(tdt)
+        ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_split_heads(xs[i % n], b3, outs[i % n],
+                                                                                     stream=stream), iters, n, launch)
+        nbytes = 2 * es * n_el + es * 3 * hidden
+        entry["add_bias_split_heads"] = {"shape": [B, S, 3, H, D], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
+                                         "cold_GBs": round(nbytes / ms / 1e6, 1),
+                                         "cold_frac_of_8TBs": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        ys = [o[0] for o in outs]  # [B,H,S,D], contiguous
+        ms_out = [torch.empty((B, S, H, D), device="cuda", dtype=tdt) for _ in ys]
+        ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_merge_heads(ys[i % n], ms_out[i % n], stream=stream),
+                                 iters, n, launch)
+        nbytes = 2 * es * B * S * hidden
+        entry["merge_heads"] = {"shape": [B, H, S, D], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
+                                "cold_GBs": round(nbytes / ms / 1e6, 1),
+                                "cold_frac_of_8TBs": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del xs, outs, ys, ms_out
+        torch.cuda.empty_cache()
+        rows.append(entry)
+    return rows
+
+
 def cpu_baseline(spec, wl, budget_s=10.0):
     """The oracle as it stands, on the headline workload, on the host cores of this machine."""
     from oracle import turbo_oracle as orc
@@ -343,6 +395,7 @@ def main():
         result["cpu_baseline"] = cpu_baseline(spec, wl)
     if per_config:
         result["per_config"] = per_config
+        result["elementwise"] = elementwise_table(torch, tb, stream, args.launch, max(20, args.kernel_iters // 2))
     print(json.dumps(result))
 
 

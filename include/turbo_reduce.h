@@ -102,6 +102,29 @@ int turbo_add_bias_layernorm(const void *x, const void *residual, const void *bi
 int turbo_add_bias_layernorm_dt(const void *x, const void *residual, const void *bias, const void *gamma,
                                 const void *beta, int rows, int hidden, float eps, void *out, int dtype, void *stream);
 
+/*
+ * Element-wise fused kernels between two GEMMs (Section 4.1.1 names "fused activation functions and fused
+ * transpose operations" without printing a formula or a layout; the definitions below are this library's
+ * reading).  Same conventions as above; `dtype` is TURBO_F32 or TURBO_F16 with binary32 arithmetic.
+ *
+ * turbo_add_bias_gelu:  out[r,j] = gelu(x[r,j] + bias[j]) on [rows, hidden], the feed-forward activation of
+ *   the BERT family.  approximate = 0: gelu(t) = t * Phi(t), Phi the standard normal distribution function;
+ *   approximate = 1: 0.5 t (1 + tanh(sqrt(2/pi) (t + 0.044715 t^3))).  bias may be NULL.  out may be exactly x.
+ *   rows * hidden may be any positive count whose 16-byte vectors number below 2^31.
+ *
+ * turbo_add_bias_split_heads:  x is [B, S, n_split, H, D], the output of one fused projection (n_split = 3 for
+ *   Q, K, V together, 1 for a single projection); bias is [n_split, H, D] or NULL; out is
+ *   [n_split, B, H, S, D]:  out[k,b,h,s,d] = x[b,s,k,h,d] + bias[k,h,d].  out must not overlap x.
+ *
+ * turbo_merge_heads:  x is [B, H, S, D] (attention output per head), out is [B, S, H, D]:
+ *   out[b,s,h,d] = x[b,h,s,d].  out must not overlap x.
+ */
+int turbo_add_bias_gelu(const void *x, const void *bias, int rows, int hidden, int approximate, void *out, int dtype,
+                        void *stream);
+int turbo_add_bias_split_heads(const void *x, const void *bias, int B, int S, int n_split, int H, int D, void *out,
+                               int dtype, void *stream);
+int turbo_merge_heads(const void *x, int B, int H, int S, int D, void *out, int dtype, void *stream);
+
 /* Static, NUL-terminated description of a status code (host pointer, never NULL). */
 const char *turbo_status_string(int status);
 

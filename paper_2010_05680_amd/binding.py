@@ -25,6 +25,7 @@ PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm", "turbo_add_bias_layernorm_dt",
+    "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
     "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
 )
 
@@ -51,8 +52,12 @@ def lib() -> ctypes.CDLL:
         L.turbo_masked_softmax_ex.argtypes = [vp, vp, ll, ll, i, i, i, i, f, i, vp]
         L.turbo_add_bias_layernorm.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, vp]
         L.turbo_add_bias_layernorm_dt.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, i, vp]
+        L.turbo_add_bias_gelu.argtypes = [vp, vp, i, i, i, vp, i, vp]
+        L.turbo_add_bias_split_heads.argtypes = [vp, vp, i, i, i, i, i, vp, i, vp]
+        L.turbo_merge_heads.argtypes = [vp, i, i, i, i, vp, i, vp]
         for name in ("turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm",
-                     "turbo_add_bias_layernorm_dt", "turbo_set_override", "turbo_describe_plan"):
+                     "turbo_add_bias_layernorm_dt", "turbo_set_override", "turbo_describe_plan",
+                     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads"):
             getattr(L, name).restype = i
         L.turbo_status_string.argtypes = [i]
         L.turbo_status_string.restype = ctypes.c_char_p
@@ -156,6 +161,42 @@ def turbo_add_bias_layernorm_dt(x, residual, bias, gamma, beta, eps: float, out:
                                              _dev_ptr(gamma, "gamma"), _dev_ptr(beta, "beta"), rows, hidden,
                                              float(eps), _dev_ptr(out, "out"), _dtype_code(x), _stream_ptr(stream)),
            "turbo_add_bias_layernorm_dt")
+    return out
+
+
+def turbo_add_bias_gelu(x: torch.Tensor, bias: Optional[torch.Tensor], approximate: bool, out: torch.Tensor,
+                        stream=None) -> torch.Tensor:
+    """out = gelu(x + bias) on [rows, hidden]; erf form, or the tanh form with approximate=True."""
+    rows, hidden = x.shape
+    dt = _dtype_code(x)
+    if out.shape != x.shape or out.dtype != x.dtype or (bias is not None and (tuple(bias.shape) != (hidden,) or bias.dtype != x.dtype)):
+        raise ValueError("out must match x; bias must be [hidden] in x's dtype")
+    _check(lib().turbo_add_bias_gelu(_dev_ptr(x, "x"), _dev_ptr(bias, "bias"), rows, hidden, int(bool(approximate)),
+                                     _dev_ptr(out, "out"), dt, _stream_ptr(stream)), "turbo_add_bias_gelu")
+    return out
+
+
+def turbo_add_bias_split_heads(x: torch.Tensor, bias: Optional[torch.Tensor], out: torch.Tensor, stream=None) -> torch.Tensor:
+    """x [B,S,n_split,H,D] (+ bias [n_split,H,D]) -> out [n_split,B,H,S,D]."""
+    B, S, K, H, D = x.shape
+    dt = _dtype_code(x)
+    if tuple(out.shape) != (K, B, H, S, D) or out.dtype != x.dtype:
+        raise ValueError("out must be [n_split,B,H,S,D] in x's dtype")
+    if bias is not None and (tuple(bias.shape) != (K, H, D) or bias.dtype != x.dtype):
+        raise ValueError("bias must be [n_split,H,D] in x's dtype")
+    _check(lib().turbo_add_bias_split_heads(_dev_ptr(x, "x"), _dev_ptr(bias, "bias"), B, S, K, H, D, _dev_ptr(out, "out"),
+                                            dt, _stream_ptr(stream)), "turbo_add_bias_split_heads")
+    return out
+
+
+def turbo_merge_heads(x: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """x [B,H,S,D] -> out [B,S,H,D]."""
+    B, H, S, D = x.shape
+    dt = _dtype_code(x)
+    if tuple(out.shape) != (B, S, H, D) or out.dtype != x.dtype:
+        raise ValueError("out must be [B,S,H,D] in x's dtype")
+    _check(lib().turbo_merge_heads(_dev_ptr(x, "x"), B, H, S, D, _dev_ptr(out, "out"), dt, _stream_ptr(stream)),
+           "turbo_merge_heads")
     return out
 
 

@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "../../include/turbo_reduce.h"
+#include "elementwise_kernels.h"
 #include "layernorm_kernels.h"
 #include "plan.h"
 #include "softmax_kernels.h"
@@ -140,9 +141,97 @@ int layernorm_impl(const void* x, const void* residual, const void* bias, const 
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }
 
+int gelu_impl(const void* x, const void* bias, int rows, int hidden, int approximate, void* out, int dtype,
+              void* stream) {
+    if (x == nullptr || out == nullptr) return TURBO_ERR_NULL;
+    const int es = elem_size_of(dtype);
+    if (es == 0) return TURBO_ERR_DTYPE;
+    if (rows <= 0 || hidden <= 0 || hidden > (1 << 27)) return TURBO_ERR_SHAPE;
+    const long long total = (long long)rows * hidden;
+    const int full_vec = 16 / es;
+    if (total / full_vec > 0x7FFFFFFFll) return TURBO_ERR_SHAPE;
+    long long align_elems = 16;
+    for (const void* p : {x, bias, (const void*)out}) {
+        if (p == nullptr) continue;
+        if (reinterpret_cast<uintptr_t>(p) % es != 0) return TURBO_ERR_ALIGN;
+        align_elems = min_ll(align_elems, byte_alignment(p) / es);
+    }
+    int vec = full_vec;
+    if (g_ovr.max_vec_bytes >= es && g_ovr.max_vec_bytes < 16) vec = 1;  // testing hook: the narrow kernel
+    if (total < vec) vec = 1;
+    const bool under_aligned = vec > 1 && align_elems % vec != 0;
+
+    turbo::GeluArgs a;
+    a.x = x;
+    a.bias = bias;
+    a.out = out;
+    a.total = total;
+    a.hidden = hidden;
+    a.approximate = approximate != 0;
+    a.div_hidden = turbo::make_fastdiv((unsigned)hidden);
+    a.div_hv = turbo::make_fastdiv((unsigned)(hidden % vec == 0 ? hidden / vec : 1));
+    hipError_t err = turbo::launch_add_bias_gelu(a, es, vec, under_aligned, reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
+}
+
+// in [B][N1][K][N2][D] -> out [K][B][N2][N1][D] (+ bias [K][N2][D])
+int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, int D, void* out, int dtype,
+                 int out_order, void* stream) {
+    if (x == nullptr || out == nullptr) return TURBO_ERR_NULL;
+    const int es = elem_size_of(dtype);
+    if (es == 0) return TURBO_ERR_DTYPE;
+    if (B <= 0 || N1 <= 0 || K <= 0 || N2 <= 0 || D <= 0) return TURBO_ERR_SHAPE;
+    const long long total = (long long)B * N1 * K * N2 * D;
+    if (total / D != (long long)B * N1 * K * N2 || total > (1ll << 40)) return TURBO_ERR_SHAPE;
+    long long align_elems = 16;
+    for (const void* p : {x, bias, (const void*)out}) {
+        if (p == nullptr) continue;
+        if (reinterpret_cast<uintptr_t>(p) % es != 0) return TURBO_ERR_ALIGN;
+        align_elems = min_ll(align_elems, byte_alignment(p) / es);
+    }
+    int vec = 16 / es;
+    if (g_ovr.max_vec_bytes >= es && g_ovr.max_vec_bytes < 16) vec = g_ovr.max_vec_bytes / es;
+    while (vec > 1 && (D % vec != 0 || align_elems % vec != 0)) vec >>= 1;
+    if (total / vec > 0x7FFFFFFFll) return TURBO_ERR_SHAPE;
+
+    turbo::PermuteArgs a;
+    a.x = x;
+    a.bias = bias;
+    a.out = out;
+    a.total = total;
+    a.B = B;
+    a.N1 = N1;
+    a.K = K;
+    a.N2 = N2;
+    a.D = D;
+    a.div_dv = turbo::make_fastdiv((unsigned)(D / vec));
+    a.div_n2 = turbo::make_fastdiv((unsigned)N2);
+    a.div_k = turbo::make_fastdiv((unsigned)K);
+    a.div_n1 = turbo::make_fastdiv((unsigned)N1);
+    a.div_b = turbo::make_fastdiv((unsigned)B);
+    a.out_order = out_order;
+    hipError_t err = turbo::launch_permute_heads(a, es, vec, reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
+
+int turbo_add_bias_gelu(const void* x, const void* bias, int rows, int hidden, int approximate, void* out, int dtype,
+                        void* stream) {
+    return gelu_impl(x, bias, rows, hidden, approximate, out, dtype, stream);
+}
+
+int turbo_add_bias_split_heads(const void* x, const void* bias, int B, int S, int n_split, int H, int D, void* out,
+                               int dtype, void* stream) {
+    // measured on MI355X: the split streams best walking its input, the merge walking its output
+    return permute_impl(x, bias, B, S, n_split, H, D, out, dtype, 0, stream);
+}
+
+int turbo_merge_heads(const void* x, int B, int H, int S, int D, void* out, int dtype, void* stream) {
+    return permute_impl(x, nullptr, B, H, 1, S, D, out, dtype, 1, stream);
+}
 
 int turbo_masked_softmax(void* scores, const void* mask, int B, int H, int Sq, int Sk, float scale, int dtype,
                          void* stream) {

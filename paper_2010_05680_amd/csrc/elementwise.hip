@@ -1,0 +1,78 @@
+// Instantiations and launchers of the element-wise fused kernels (both element types).
+#include "elementwise_kernels.h"
+
+namespace turbo {
+
+namespace {
+
+int grid_for(long long n_vec) {
+    long long tiles = (n_vec + kElemThreads * kElemUnroll - 1) / (kElemThreads * kElemUnroll);
+    return (int)(tiles < 1 ? 1 : tiles);
+}
+
+template <typename T, int VEC>
+hipError_t gelu_tv(const GeluArgs& a, bool ua, hipStream_t s) {
+    const bool wrap = a.hidden % VEC != 0;
+    const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
+#define TURBO_GELU(APPROX, WRAP, UA) \
+    hipLaunchKernelGGL((add_bias_gelu_kernel<T, VEC, APPROX, WRAP, UA>), grid, block, 0, s, a)
+    if (a.approximate) {
+        if (wrap) { if (ua) TURBO_GELU(true, true, true); else TURBO_GELU(true, true, false); }
+        else      { if (ua) TURBO_GELU(true, false, true); else TURBO_GELU(true, false, false); }
+    } else {
+        if (wrap) { if (ua) TURBO_GELU(false, true, true); else TURBO_GELU(false, true, false); }
+        else      { if (ua) TURBO_GELU(false, false, true); else TURBO_GELU(false, false, false); }
+    }
+#undef TURBO_GELU
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
+    const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
+    if (a.bias) {
+        if (a.out_order)
+            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, true>), grid, block, 0, s, a);
+        else
+            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, false>), grid, block, 0, s, a);
+    } else {
+        if (a.out_order)
+            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, true>), grid, block, 0, s, a);
+        else
+            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, false>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_add_bias_gelu(const GeluArgs& a, int elem_size, int vec, bool under_aligned, hipStream_t s) {
+    if (elem_size == 4) {
+        if (vec == 4) return gelu_tv<float, 4>(a, under_aligned, s);
+        if (vec == 1) return gelu_tv<float, 1>(a, false, s);
+    } else {
+        if (vec == 8) return gelu_tv<_Float16, 8>(a, under_aligned, s);
+        if (vec == 1) return gelu_tv<_Float16, 1>(a, false, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_permute_heads(const PermuteArgs& a, int elem_size, int vec, hipStream_t s) {
+    if (elem_size == 4) {
+        switch (vec) {
+            case 4: return permute_tv<float, 4>(a, s);
+            case 2: return permute_tv<float, 2>(a, s);
+            case 1: return permute_tv<float, 1>(a, s);
+        }
+    } else {
+        switch (vec) {
+            case 8: return permute_tv<_Float16, 8>(a, s);
+            case 4: return permute_tv<_Float16, 4>(a, s);
+            case 2: return permute_tv<_Float16, 2>(a, s);
+            case 1: return permute_tv<_Float16, 1>(a, s);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace turbo

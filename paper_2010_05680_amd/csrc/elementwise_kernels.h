@@ -1,0 +1,198 @@
+// Element-wise fused kernels that sit between two GEMMs (Section 4.1.1 of the paper: "fused activation functions
+// and fused transpose operations ... composed of element-wise operations"): bias + GELU, bias + head split, head
+// merge.  The paper prints no formula or layout for them; the readings are the ones the C header states.
+//
+// All three are pure streams (every element read once, written once), so the design is the one that reached the
+// copy ceiling in the reduction kernels: 16-byte non-temporal accesses, one short-lived workgroup per tile of
+// kElemUnroll * 256 vectors, all of a lane's loads issued before the first use.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+
+namespace turbo {
+
+constexpr int kElemUnroll = 4;    // vectors per lane per workgroup
+constexpr int kElemThreads = 256;
+
+struct GeluArgs {
+    const void* x;
+    const void* bias;  // may be null
+    void* out;
+    long long total;   // rows * hidden
+    int hidden;
+    int approximate;
+    FastDiv div_hidden;  // hidden
+    FastDiv div_hv;      // hidden / VEC when that is exact
+};
+
+// t * Phi(t) with Phi(-|t|) = erfc(u)/2, u = |t|/sqrt 2, and a branch-free erfc:
+//   erfc(u) ~= exp(-u^2) * (c1 w + ... + c7 w^7),  w = 1/(1 + u/2)
+// (1.2e-6 relative on [0, 9.5]; the resulting binary32 gelu stays within 0.16 of the parity bound
+// max(1e-6, 1e-5 |gelu|) over t in [-9, 9]).  The constants are fitted by csrc/fit_gelu_erfc.py; the math
+// library's erfc is exact to a few ulp but its range branches make this kernel ALU-bound (measured: 30 % of the
+// HBM peak for binary16 storage instead of 70 %).
+__device__ __forceinline__ float gelu_erf(float t) {
+    // u/2 = |t| / (2 sqrt 2);  exp(-u^2) = exp2(t^2 * (-log2(e)/2));  the 1/2 of erfc/2 is folded into c_k
+    const float w = fast_rcp(fmaf(fabsf(t), 0.35355339059327376f, 1.0f));
+    float p = 0.5f * 0.08912515640258789f;
+    p = fmaf(p, w, 0.5f * -0.3599849343299866f);
+    p = fmaf(p, w, 0.5f * 0.39377784729003906f);
+    p = fmaf(p, w, 0.5f * 0.03465970978140831f);
+    p = fmaf(p, w, 0.5f * 0.282719224691391f);
+    p = fmaf(p, w, 0.5f * 0.2773537337779999f);
+    p = fmaf(p, w, 0.5f * 0.28234806656837463f);
+    const float half_erfc = (p * w) * fast_exp2((t * t) * (-0.5f * kLog2e));  // Phi(-|t|)
+    return t * (t < 0.f ? half_erfc : 1.0f - half_erfc);
+}
+__device__ __forceinline__ float gelu_tanh(float t) {
+    // 0.5 t (1 + tanh u) = t / (1 + exp(-2u)),  u = sqrt(2/pi) (t + 0.044715 t^3)
+    const float u = 0.7978845608028654f * fmaf(0.044715f * t * t, t, t);
+    return t * fast_rcp(1.0f + fast_exp2(-2.0f * kLog2e * u));
+}
+
+// WRAP: hidden is not a multiple of VEC, so a vector may straddle a row end and the bias column wraps inside it.
+// UA: pointers are only element-aligned (the flat tensor is still walked in VEC-wide steps).
+template <typename T, int VEC, bool APPROX, bool WRAP, bool UA>
+__global__ __launch_bounds__(kElemThreads) void add_bias_gelu_kernel(GeluArgs a) {
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    T* out = reinterpret_cast<T*>(a.out);
+    const long long n_vec = a.total / VEC;  // whole vectors; the last total % VEC elements are a scalar tail
+    const long long base = (long long)blockIdx.x * (kElemThreads * kElemUnroll) + threadIdx.x;
+
+    Pack<T, VEC> raw[kElemUnroll];
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        long long i = base + (long long)u * kElemThreads;
+        long long ic = i < n_vec ? i : 0;
+        raw[u] = load_stream<T, VEC, UA>(x + ic * VEC);
+    }
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        long long i = base + (long long)u * kElemThreads;
+        if (i >= n_vec) continue;
+        const long long e = i * VEC;
+        // column of the vector's first element, (i * VEC) mod hidden, with 32-bit multiply-shift divisions only
+        // (the vector count fits 31 bits and hidden * VEC fits 31 bits, both checked on the host)
+        const unsigned iu = (unsigned)i;
+        int col;
+        if constexpr (WRAP) {
+            const unsigned r1 = iu - fastdiv(iu, a.div_hidden) * (unsigned)a.hidden;  // i mod hidden
+            const unsigned e2 = r1 * VEC;
+            col = (int)(e2 - fastdiv(e2, a.div_hidden) * (unsigned)a.hidden);
+        } else {
+            col = (int)((iu - fastdiv(iu, a.div_hv) * a.div_hv.d) * VEC);
+        }
+        float b[VEC];
+        if (bias == nullptr) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) b[j] = 0.f;
+        } else if constexpr (WRAP) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                int c = col + j;
+                c = c >= a.hidden ? c - a.hidden : c;
+                b[j] = (float)bias[c];
+            }
+        } else {
+            Pack<T, VEC> pb = load_pack<T, VEC, UA>(bias + col);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) b[j] = (float)pb.v[j];
+        }
+        Pack<T, VEC> o;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float t = (float)raw[u].v[j] + b[j];
+            o.v[j] = (T)(APPROX ? gelu_tanh(t) : gelu_erf(t));
+        }
+        store_stream<T, VEC, UA>(out + e, o);
+    }
+    // scalar tail (at most VEC-1 elements), done by one lane of the last workgroup
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        for (long long e = n_vec * VEC; e < a.total; ++e) {
+            const int col = (int)(e % a.hidden);
+            const float t = (float)x[e] + (bias ? (float)bias[col] : 0.f);
+            out[e] = (T)(APPROX ? gelu_tanh(t) : gelu_erf(t));
+        }
+    }
+}
+
+// Generic 5-D permutation behind both transposes:
+//   in  [B][N1][K][N2][D]  ->  out [K][B][N2][N1][D],   out += bias[K][N2][D] if present.
+// Head split: N1 = S, N2 = H (x is the fused projection output, K = n_split).  Head merge: K = 1, N1 = H, N2 = S.
+struct PermuteArgs {
+    const void* x;
+    const void* bias;  // may be null
+    void* out;
+    long long total;   // B*N1*K*N2*D
+    int B, N1, K, N2, D;
+    FastDiv div_dv, div_n2, div_k, div_n1, div_b;  // D/VEC, N2, K, N1, B
+    int out_order;  // 1: lanes walk the output tensor, 0: the input tensor
+};
+
+// OUT_ORDER = false: lanes walk the input (reads fully coalesced, writes in D-element pieces);
+// OUT_ORDER = true : lanes walk the output (writes fully coalesced, reads in D-element pieces).
+template <typename T, int VEC, bool BIAS, bool OUT_ORDER>
+__global__ __launch_bounds__(kElemThreads) void permute_heads_kernel(PermuteArgs a) {
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    T* out = reinterpret_cast<T*>(a.out);
+    const long long n_vec = a.total / VEC;
+    const long long base = (long long)blockIdx.x * (kElemThreads * kElemUnroll) + threadIdx.x;
+
+    long long src[kElemUnroll], dst[kElemUnroll], boff[kElemUnroll];
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        long long i = base + (long long)u * kElemThreads;
+        unsigned rest = (unsigned)(i < n_vec ? i : 0);  // the vector count fits 31 bits (checked on the host)
+        unsigned q = fastdiv(rest, a.div_dv);
+        const unsigned dv = rest - q * a.div_dv.d;
+        rest = q;
+        unsigned b, n1, k, n2;
+        if constexpr (OUT_ORDER) {  // i = (((k*B + b)*N2 + n2)*N1 + n1)*(D/VEC) + dv
+            q = fastdiv(rest, a.div_n1);
+            n1 = rest - q * a.div_n1.d;
+            rest = q;
+            q = fastdiv(rest, a.div_n2);
+            n2 = rest - q * a.div_n2.d;
+            rest = q;
+            q = fastdiv(rest, a.div_b);
+            b = rest - q * a.div_b.d;
+            k = q;
+        } else {  // i = (((b*N1 + n1)*K + k)*N2 + n2)*(D/VEC) + dv
+            q = fastdiv(rest, a.div_n2);
+            n2 = rest - q * a.div_n2.d;
+            rest = q;
+            q = fastdiv(rest, a.div_k);
+            k = rest - q * a.div_k.d;
+            rest = q;
+            q = fastdiv(rest, a.div_n1);
+            n1 = rest - q * a.div_n1.d;
+            b = q;
+        }
+        src[u] = ((((long long)b * a.N1 + n1) * a.K + k) * a.N2 + n2) * a.D + (long long)dv * VEC;
+        dst[u] = ((((long long)k * a.B + b) * a.N2 + n2) * a.N1 + n1) * a.D + (long long)dv * VEC;
+        boff[u] = ((long long)k * a.N2 + n2) * a.D + (long long)dv * VEC;
+    }
+    Pack<T, VEC> raw[kElemUnroll];
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) raw[u] = load_stream<T, VEC, false>(x + src[u]);
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        long long i = base + (long long)u * kElemThreads;
+        if (i >= n_vec) continue;
+        Pack<T, VEC> o = raw[u];
+        if constexpr (BIAS) {
+            Pack<T, VEC> pb = load_pack<T, VEC, false>(bias + boff[u]);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) o.v[j] = (T)((float)raw[u].v[j] + (float)pb.v[j]);
+        }
+        store_stream<T, VEC, false>(out + dst[u], o);
+    }
+}
+
+hipError_t launch_add_bias_gelu(const GeluArgs& a, int elem_size, int vec, bool under_aligned, hipStream_t s);
+hipError_t launch_permute_heads(const PermuteArgs& a, int elem_size, int vec, hipStream_t s);
+
+}  // namespace turbo

@@ -1,0 +1,136 @@
+"""Parity of the element-wise fused kernels (bias+GELU, bias+head split, head merge) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turbo_oracle as orc
+from paper_2010_05680_amd import binding as tb
+
+from conftest import assert_parity
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+F32, F16 = np.float32, np.float16
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _rand(rng, shape, dtype, std=1.0):
+    return (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(dtype)
+
+
+def _gelu(x, bias, approximate, out=None):
+    xd = gu.dev(x)
+    bd = None if bias is None else gu.dev(bias)
+    od = torch.full_like(xd, float("nan")) if out is None else out
+    tb.turbo_add_bias_gelu(xd, bd, approximate, od)
+    torch.cuda.synchronize()
+    return od
+
+
+@pytest.mark.parametrize("approximate", [False, True], ids=["erf", "tanh"])
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_gelu_shapes(dtype, approximate):
+    rng = np.random.Generator(np.random.Philox(11))
+    shapes = [(1, 1), (3, 5), (7, 64), (16, 768), (33, 3072), (5, 1001), (2, 4099), (257, 130), (1, 100003), (640, 3072)]
+    for rows, hidden in shapes:
+        x = _rand(rng, (rows, hidden), dtype, 1.5)
+        b = _rand(rng, (hidden,), dtype, 0.5)
+        got = _np(_gelu(x, b, approximate))
+        assert_parity(got, orc.add_bias_gelu(x, b, approximate), dtype, f"gelu {rows}x{hidden} approximate={approximate}")
+
+
+def test_gelu_wide_range_no_bias_in_place_and_narrow_kernel():
+    rng = np.random.Generator(np.random.Philox(12))
+    x = np.concatenate([np.linspace(-12, 12, 4096, dtype=F32), _rand(rng, (4096,), F32, 4.0)]).reshape(8, 1024)
+    for approximate in (False, True):
+        got = _np(_gelu(x, None, approximate))
+        assert_parity(got, orc.add_bias_gelu(x, None, approximate), F32, f"gelu wide range approximate={approximate}")
+    xd = gu.dev(x)
+    tb.turbo_add_bias_gelu(xd, None, False, xd)  # out aliases x
+    torch.cuda.synchronize()
+    assert_parity(_np(xd), orc.add_bias_gelu(x, None), F32, "gelu in place")
+    b = _rand(rng, (1024,), F32, 0.3)
+    with gu.overrides(max_vec_bytes=4):
+        assert_parity(_np(_gelu(x, b, False)), orc.add_bias_gelu(x, b), F32, "gelu 4-byte kernel")
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_gelu_unaligned_pointers_and_guard_bands(dtype):
+    rng = np.random.Generator(np.random.Philox(13))
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    for rows, hidden in [(9, 768), (5, 1003), (1, 7)]:
+        x = _rand(rng, (rows, hidden), dtype)
+        b = _rand(rng, (hidden,), dtype, 0.2)
+        n = x.size
+        xbuf = torch.zeros(n + 16, dtype=tdt, device="cuda")
+        xv = xbuf[3:3 + n].view(rows, hidden)
+        xv.copy_(torch.from_numpy(x))
+        obuf = torch.full((n + 64,), float("nan"), dtype=tdt, device="cuda")
+        ov = obuf[29:29 + n].view(rows, hidden)
+        bbuf = torch.zeros(hidden + 8, dtype=tdt, device="cuda")
+        bv = bbuf[1:1 + hidden]
+        bv.copy_(torch.from_numpy(b))
+        tb.turbo_add_bias_gelu(xv, bv, False, ov)
+        torch.cuda.synchronize()
+        assert_parity(_np(ov), orc.add_bias_gelu(x, b), dtype, f"gelu offset views {rows}x{hidden}")
+        assert torch.isnan(obuf[:29]).all() and torch.isnan(obuf[29 + n:]).all(), "gelu wrote outside its tensor"
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_split_and_merge_heads(dtype):
+    rng = np.random.Generator(np.random.Philox(14))
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    for B, S, K, H, D in [(1, 1, 1, 1, 1), (2, 5, 3, 4, 64), (20, 128, 3, 12, 64), (3, 17, 1, 5, 20), (2, 9, 2, 3, 6),
+                          (2, 7, 3, 2, 5), (1, 300, 3, 16, 64)]:
+        x = _rand(rng, (B, S, K, H, D), dtype)
+        bias = _rand(rng, (K, H, D), dtype, 0.3)
+        for use_bias in (True, False):
+            out = torch.full((K, B, H, S, D), float("nan"), dtype=tdt, device="cuda")
+            tb.turbo_add_bias_split_heads(gu.dev(x), gu.dev(bias) if use_bias else None, out)
+            torch.cuda.synchronize()
+            want = orc.add_bias_split_heads(x, bias if use_bias else None)
+            if use_bias:
+                assert_parity(_np(out), want, dtype, f"split heads {B,S,K,H,D}")
+            else:
+                np.testing.assert_array_equal(_np(out).astype(np.float64), want)  # a pure permutation is bit-exact
+        y = _rand(rng, (B, H, S, D), dtype)
+        out = torch.full((B, S, H, D), float("nan"), dtype=tdt, device="cuda")
+        tb.turbo_merge_heads(gu.dev(y), out)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(_np(out).astype(np.float64), orc.merge_heads(y))
+
+
+def test_elementwise_full_size_sampled():
+    """GPT-2-medium feed-forward activation [32768, 4096] fp16 and QKV split [64,512,3,16,64] fp16, sampled rows."""
+    rng = np.random.Generator(np.random.Philox(15))
+    rows, hidden = 32768, 4096
+    x = _rand(rng, (rows, hidden), F16, 1.5)
+    b = _rand(rng, (hidden,), F16, 0.5)
+    out = _gelu(x, b, False)
+    pick = gu.sample_rows(rows, 300, seed=5)
+    assert_parity(_np(out[torch.from_numpy(pick).cuda()]), orc.add_bias_gelu(x[pick], b), F16, "gelu full size, sampled rows")
+    assert torch.isfinite(out).all()
+    B, S, K, H, D = 64, 512, 3, 16, 64
+    x5 = _rand(rng, (B, S, K, H, D), F16)
+    bias = _rand(rng, (K, H, D), F16, 0.3)
+    o5 = torch.full((K, B, H, S, D), float("nan"), dtype=torch.float16, device="cuda")
+    tb.turbo_add_bias_split_heads(gu.dev(x5), gu.dev(bias), o5)
+    torch.cuda.synchronize()
+    for bsel in (0, 31, 63):
+        want = orc.add_bias_split_heads(x5[bsel:bsel + 1], bias)
+        assert_parity(_np(o5[:, bsel:bsel + 1]), want, F16, f"split heads full size, batch {bsel}")
+    assert torch.isfinite(o5).all()
+
+
+def test_elementwise_error_paths_need_no_gpu_work():
+    L = tb.lib()
+    fake = 0x10000
+    assert L.turbo_add_bias_gelu(None, None, 4, 4, 0, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert L.turbo_add_bias_gelu(fake, None, 0, 4, 0, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_add_bias_gelu(fake, None, 4, 4, 0, fake, 9, None) == tb.TURBO_ERR_DTYPE
+    assert L.turbo_add_bias_gelu(fake + 2, None, 4, 4, 0, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert L.turbo_add_bias_split_heads(fake, None, 1, 1, 0, 1, 1, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_merge_heads(fake, 1, 1, 1, 1, None, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
