@@ -110,12 +110,12 @@ __device__ __forceinline__ void load_bias(const T* p, int col, float (&dst)[VEC]
 // persistent ones that keep the parameters across tiles.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC, int G, int NV, bool RES, int MODE>
-__global__ __launch_bounds__(256) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
+__global__ __launch_bounds__(64 * kWaveFamilyWaves) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
     constexpr int GPW = kWave / G;
-    constexpr int kWaves = 4;
+    constexpr int kWaves = kWaveFamilyWaves;
     constexpr int TILE_ROWS = R * GPW * kWaves;
     constexpr int STEPS = log2_c(G) > 0 ? log2_c(G) : 1;
     constexpr bool PRELOAD = NV * VEC <= kParamPreloadElems;
@@ -512,9 +512,10 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
 template <typename T, int VEC, int G, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
-    constexpr int TILE_ROWS = R * (kWave / G) * 4;
+    constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>), dim3(n_tiles), dim3(256), 0, s, a, n_tiles);
+    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>), dim3(n_tiles), dim3(64 * kWaveFamilyWaves), 0, s, a,
+                       n_tiles);
     return hipGetLastError();
 }
 

@@ -25,6 +25,10 @@ enum RowMode { kModeFull = 0, kModeRagged = 1, kModeUnder = 2 };
 constexpr int kMaxNV = 16;                 // most vectors a lane keeps in registers
 constexpr int kWaveMaxVecs = 64 * kMaxNV;  // longest row (in vectors) a single wavefront may own
 constexpr int kBlockMaxWaves = 16;
+#ifndef TURBO_WAVE_FAMILY_WAVES
+#define TURBO_WAVE_FAMILY_WAVES 4
+#endif
+constexpr int kWaveFamilyWaves = TURBO_WAVE_FAMILY_WAVES;  // wavefronts per workgroup in the wave family
 constexpr int kStreamThreads = 1024;
 
 // Register budgets, in row elements held per lane, that bound each family.

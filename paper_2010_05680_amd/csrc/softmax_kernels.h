@@ -85,12 +85,12 @@ __device__ __forceinline__ int vec_overlap(int col, int row_len) {
 // instruction of a wavefront covers 64/G consecutive rows in 16*G-byte pieces.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
-__global__ __launch_bounds__(256) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
+__global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int GPW = kWave / G;  // lane groups per wavefront
-    constexpr int kWaves = 4;
+    constexpr int kWaves = kWaveFamilyWaves;
     constexpr int TILE_ROWS = R * GPW * kWaves;
 
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
@@ -379,10 +379,10 @@ inline int capped_grid(long long work_items, int waves_per_block, int default_ca
 template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
 hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
-    constexpr int TILE_ROWS = R * (kWave / G) * 4;
+    constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK, MODE>), dim3(capped_grid(n_tiles, 4, kSoftmaxWaveCap, lc)),
-                       dim3(256), 0, s, a, n_tiles);
+    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
+                       dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 
