@@ -26,6 +26,7 @@ PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 EXPORTED_SYMBOLS = (
     "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm", "turbo_add_bias_layernorm_dt",
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
+    "turbo_batch_schedule", "turbo_mem_plan",
     "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
 )
 

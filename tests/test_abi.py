@@ -11,15 +11,17 @@ import torch
 from paper_2010_05680_amd import binding as tb
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "turbo_reduce.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("turbo_reduce.h", "turbo_serving.h")]
 
 FAKE = 0x10000  # a non-null, 16-byte aligned "device pointer"; validation must fail before it is used
 
 
 def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(turbo_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(turbo_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
