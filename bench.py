@@ -223,6 +223,31 @@ def elementwise_table(torch, tb, stream, launch, iters):
     return rows
 
 
+def varlen_table(torch, tb, wl, stream, launch, iters):
+    """Config 2 (zero-padded variable-length batch) through the length-aware entry points: the same tensors, but
+    padding is neither read nor written.  Bytes are the ones actually moved: per head, a request of length n reads
+    n*n scores and writes n*Smax; LayerNorm touches n of the Smax token rows."""
+    spec = wl.config_spec(2)
+    ks = KernelSets(spec, torch, tb, wl)
+    lens = torch.from_numpy(spec.lengths.astype(np.int32)).cuda()
+    B, S, H, hid, es = spec.B, spec.Sk, spec.H, spec.hidden, 4
+    sm_bytes = int(sum(es * H * (n * n + n * S) for n in spec.lengths)) + 4 * B
+    ln_bytes = int(sum(3 * es * n * hid for n in spec.lengths)) + 3 * es * hid + 4 * B
+    view = lambda t: t.view(B, S, hid)
+    rows = {}
+    for name, fn, per, nbytes, padded_bytes in (
+            ("softmax", lambda i: tb.turbo_masked_softmax_varlen(ks.scores[i % ks.n_sm_sets], lens, lens, spec.scale,
+                                                                stream=stream), ks.n_sm_sets, sm_bytes, ks.softmax_bytes),
+            ("layernorm", lambda i: tb.turbo_add_bias_layernorm_varlen(
+                view(ks.x[i % ks.n_ln_sets]), view(ks.res[i % ks.n_ln_sets]), ks.bias, ks.gamma, ks.beta, lens, spec.eps,
+                view(ks.out[i % ks.n_ln_sets]), stream=stream), ks.n_ln_sets, ln_bytes, ks.layernorm_bytes)):
+        ms, _, _ = time_launches(torch, stream, fn, iters, per, launch)
+        rows[name] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1),
+                      "padded_bytes": padded_bytes, "real_fraction_of_padded_bytes": round(nbytes / padded_bytes, 3)}
+    rows["lengths"] = [int(v) for v in spec.lengths]
+    return rows
+
+
 def cpu_baseline(spec, wl, budget_s=10.0):
     """The oracle as it stands, on the headline workload, on the host cores of this machine."""
     from oracle import turbo_oracle as orc
@@ -396,6 +421,7 @@ def main():
     if per_config:
         result["per_config"] = per_config
         result["elementwise"] = elementwise_table(torch, tb, stream, args.launch, max(20, args.kernel_iters // 2))
+        result["length_aware_config2"] = varlen_table(torch, tb, wl, stream, args.launch, max(20, args.kernel_iters // 2))
     print(json.dumps(result))
 
 

@@ -80,6 +80,23 @@ int turbo_masked_softmax_ex(void *scores, const void *mask, long long mask_strid
                             int H, int Sq, int Sk, float scale, int dtype, void *stream);
 
 /*
+ * Length-aware variant for zero-padded variable-length batches (Section 2.1: short sequences are padded to the
+ * longest one of the batch; the paper's kernels then work on the padding too).  Instead of an additive mask the
+ * caller passes the request lengths, and the kernel neither reads nor normalises what lies beyond them:
+ *
+ *   for q < q_lengths[b]:  scores[b,h,q,k] <- softmax over k < k_lengths[b] of scale*scores[b,h,q,k],
+ *                          scores[b,h,q,k] <- 0 for k >= k_lengths[b];
+ *   rows q >= q_lengths[b] are left untouched.
+ *
+ * For real rows this equals turbo_masked_softmax_ex with a 0 / -10000 key mask (where exp() underflows to the
+ * same exact zeros).  k_lengths, q_lengths: DEVICE int32 arrays [B]; q_lengths may be NULL (all Sq rows are
+ * computed); for self-attention pass the same array twice.  Lengths are clamped to 0..Sk; a request with
+ * k_lengths[b] = 0 is left untouched.  Rows of more than 32768 elements are not supported (TURBO_ERR_SHAPE).
+ */
+int turbo_masked_softmax_varlen(void *scores, const int *q_lengths, const int *k_lengths, int B, int H, int Sq, int Sk,
+                                float scale, int dtype, void *stream);
+
+/*
  * Fused bias add + residual add + LayerNorm (the "AddBiasLayerNorm" kernel of
  * Section 6.2.1; Section 4.1.2 and Equation 1: LayerNorm reduces a mean and a
  * population variance per row), binary32 tensors:
@@ -101,6 +118,15 @@ int turbo_add_bias_layernorm(const void *x, const void *residual, const void *bi
 /* The same operation with all six tensors stored in `dtype` (TURBO_F32 or TURBO_F16). */
 int turbo_add_bias_layernorm_dt(const void *x, const void *residual, const void *bias, const void *gamma,
                                 const void *beta, int rows, int hidden, float eps, void *out, int dtype, void *stream);
+
+/*
+ * Length-aware variant for zero-padded variable-length batches: x, residual, out are [B, S, hidden]; token rows
+ * (b, s) with s >= lengths[b] are padding and are neither read nor written (out keeps whatever it held there);
+ * all other rows are computed exactly as by turbo_add_bias_layernorm_dt.  lengths: DEVICE int32 array [B].
+ */
+int turbo_add_bias_layernorm_varlen(const void *x, const void *residual, const void *bias, const void *gamma,
+                                    const void *beta, const int *lengths, int B, int S, int hidden, float eps,
+                                    void *out, int dtype, void *stream);
 
 /*
  * Element-wise fused kernels between two GEMMs (Section 4.1.1 names "fused activation functions and fused

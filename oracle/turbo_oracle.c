@@ -213,3 +213,55 @@ void oracle_merge_heads(const double *x, int B, int H, int S, int D, double *out
                 for (int d = 0; d < D; ++d)
                     out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];
 }
+
+/* ---- length-aware variants for zero-padded variable-length batches (Section 2.1) -----------------------
+ * The paper pads short requests to the longest one and lets its kernels work on the padding.  These variants
+ * take the request lengths instead: what lies beyond a request's length is neither read nor normalised.
+ * out is a full copy of the input for everything the operation leaves untouched. */
+
+/* For q < q_len[b] (all q if q_len is NULL) and k_len[b] > 0: softmax over the first k_len[b] keys of
+ * scale * scores, exact zeros for the remaining keys.  All other rows: out = scores. */
+void oracle_masked_softmax_varlen(const double *scores, const int *q_len, const int *k_len, int B, int H, int Sq,
+                                  int Sk, double scale, double *out)
+{
+    for (int b = 0; b < B; ++b) {
+        int kl = k_len[b] < 0 ? 0 : (k_len[b] > Sk ? Sk : k_len[b]);
+        for (int h = 0; h < H; ++h)
+            for (int q = 0; q < Sq; ++q) {
+                long long row = ((long long)b * H + h) * Sq + q;
+                const double *s = scores + row * Sk;
+                double *y = out + row * Sk;
+                int active = kl > 0 && (q_len == NULL || q < q_len[b]);
+                if (!active) {
+                    for (int k = 0; k < Sk; ++k) y[k] = s[k];
+                    continue;
+                }
+                double m = -INFINITY, l = 0.0;
+                for (int k = 0; k < kl; ++k)
+                    if (scale * s[k] > m) m = scale * s[k];
+                for (int k = 0; k < kl; ++k) {
+                    y[k] = exp(scale * s[k] - m);
+                    l += y[k];
+                }
+                for (int k = 0; k < kl; ++k) y[k] /= l;
+                for (int k = kl; k < Sk; ++k) y[k] = 0.0;
+            }
+    }
+}
+
+/* x, residual, out_before, out are [B][S][hidden].  Token rows s < len[b] get LayerNorm(x + bias + residual)
+ * * gamma + beta; padding rows keep out_before. */
+void oracle_add_bias_layernorm_varlen(const double *x, const double *residual, const double *bias,
+                                      const double *gamma, const double *beta, const int *len, int B, int S,
+                                      int hidden, double eps, const double *out_before, double *out)
+{
+    for (int b = 0; b < B; ++b)
+        for (int s = 0; s < S; ++s) {
+            long long r = (long long)b * S + s;
+            if (s < len[b])
+                oracle_add_bias_layernorm(x + r * hidden, residual ? residual + r * hidden : NULL, bias, gamma, beta, 1,
+                                          hidden, eps, out + r * hidden);
+            else
+                for (int j = 0; j < hidden; ++j) out[r * hidden + j] = out_before[r * hidden + j];
+        }
+}

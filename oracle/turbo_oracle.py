@@ -54,6 +54,13 @@ def _load():
             f.restype = ctypes.c_double
         lib.oracle_welford_merge.argtypes = [ctypes.c_double] * 6 + [_dp] * 3
         lib.oracle_welford_merge.restype = None
+        _ip = ctypes.POINTER(ctypes.c_int)
+        lib.oracle_masked_softmax_varlen.argtypes = [_dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_double, _dp]
+        lib.oracle_masked_softmax_varlen.restype = None
+        lib.oracle_add_bias_layernorm_varlen.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int,
+                                                         ctypes.c_int, ctypes.c_double, _dp, _dp]
+        lib.oracle_add_bias_layernorm_varlen.restype = None
         lib.oracle_add_bias_gelu.argtypes = [_dp, _dp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, _dp]
         lib.oracle_add_bias_gelu.restype = None
         lib.oracle_add_bias_split_heads.argtypes = [_dp, _dp] + [ctypes.c_int] * 5 + [_dp]
@@ -185,4 +192,44 @@ def merge_heads(x) -> np.ndarray:
     out = np.empty((B, S, H, D), dtype=np.float64)
     if xx.size:
         _load().oracle_merge_heads(_ptr(xx), B, H, S, D, _ptr(out))
+    return out
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _iptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+
+
+def masked_softmax_varlen(scores, q_lengths, k_lengths, scale: float = 1.0) -> np.ndarray:
+    """Length-aware softmax on [B,H,Sq,Sk]: rows q < q_lengths[b] are normalised over their first k_lengths[b]
+    keys (exact zeros after); every other row is returned unchanged.  q_lengths may be None (all rows)."""
+    s = _f64(scores)
+    B, H, Sq, Sk = s.shape
+    kl = _i32(k_lengths)
+    ql = None if q_lengths is None else _i32(q_lengths)
+    if kl.shape != (B,) or (ql is not None and ql.shape != (B,)):
+        raise ValueError("lengths must be [B]")
+    out = np.empty_like(s)
+    if s.size:
+        _load().oracle_masked_softmax_varlen(_ptr(s), _iptr(ql), _iptr(kl), B, H, Sq, Sk, float(scale), _ptr(out))
+    return out
+
+
+def add_bias_layernorm_varlen(x, residual, bias, gamma, beta, lengths, eps: float, out_before) -> np.ndarray:
+    """Length-aware add-bias-LayerNorm on [B,S,hidden]: rows s < lengths[b] are computed, the rest keep out_before."""
+    xx = _f64(x)
+    B, S, hidden = xx.shape
+    rr = None if residual is None else _f64(residual)
+    bb = None if bias is None else _f64(bias)
+    gg, be = _f64(gamma), _f64(beta)
+    ob = _f64(out_before)
+    ln = _i32(lengths)
+    if ob.shape != xx.shape or ln.shape != (B,):
+        raise ValueError("shape")
+    out = np.empty_like(xx)
+    _load().oracle_add_bias_layernorm_varlen(_ptr(xx), _ptr(rr), _ptr(bb), _ptr(gg), _ptr(be), _iptr(ln), B, S, hidden,
+                                             float(eps), _ptr(ob), _ptr(out))
     return out

@@ -24,7 +24,8 @@ TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES = 0, 1, 2
 PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
-    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm", "turbo_add_bias_layernorm_dt",
+    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_add_bias_layernorm",
+    "turbo_add_bias_layernorm_dt", "turbo_add_bias_layernorm_varlen",
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
     "turbo_batch_schedule", "turbo_mem_plan",
     "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
@@ -51,13 +52,17 @@ def lib() -> ctypes.CDLL:
         vp, i, ll, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_float
         L.turbo_masked_softmax.argtypes = [vp, vp, i, i, i, i, f, i, vp]
         L.turbo_masked_softmax_ex.argtypes = [vp, vp, ll, ll, i, i, i, i, f, i, vp]
+        L.turbo_masked_softmax_varlen.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp]
+        L.turbo_masked_softmax_varlen.restype = i
         L.turbo_add_bias_layernorm.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, vp]
         L.turbo_add_bias_layernorm_dt.argtypes = [vp, vp, vp, vp, vp, i, i, f, vp, i, vp]
+        L.turbo_add_bias_layernorm_varlen.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, f, vp, i, vp]
+        L.turbo_add_bias_layernorm_varlen.restype = i
         L.turbo_add_bias_gelu.argtypes = [vp, vp, i, i, i, vp, i, vp]
         L.turbo_add_bias_split_heads.argtypes = [vp, vp, i, i, i, i, i, vp, i, vp]
         L.turbo_merge_heads.argtypes = [vp, i, i, i, i, vp, i, vp]
         for name in ("turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_add_bias_layernorm",
-                     "turbo_add_bias_layernorm_dt", "turbo_set_override", "turbo_describe_plan",
+                     "turbo_add_bias_layernorm_dt", "turbo_add_bias_layernorm_varlen", "turbo_set_override", "turbo_describe_plan",
                      "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads"):
             getattr(L, name).restype = i
         L.turbo_status_string.argtypes = [i]
@@ -134,6 +139,25 @@ def turbo_masked_softmax_ex(scores: torch.Tensor, mask: Optional[torch.Tensor], 
     return scores
 
 
+def _lengths_ptr(t: Optional[torch.Tensor], B: int, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if t.dtype != torch.int32 or tuple(t.shape) != (B,):
+        raise ValueError(f"{name} must be an int32 tensor of shape [B]")
+    return _dev_ptr(t, name)
+
+
+def turbo_masked_softmax_varlen(scores: torch.Tensor, q_lengths: Optional[torch.Tensor], k_lengths: torch.Tensor,
+                                scale: float, stream=None) -> torch.Tensor:
+    """In-place length-aware softmax: keys beyond k_lengths[b] get weight 0 unread, rows beyond q_lengths[b] are skipped."""
+    B, H, Sq, Sk = scores.shape
+    dt = _dtype_code(scores)
+    _check(lib().turbo_masked_softmax_varlen(_dev_ptr(scores, "scores"), _lengths_ptr(q_lengths, B, "q_lengths"),
+                                             _lengths_ptr(k_lengths, B, "k_lengths"), B, H, Sq, Sk, float(scale), dt,
+                                             _stream_ptr(stream)), "turbo_masked_softmax_varlen")
+    return scores
+
+
 def _layernorm_args(x, residual, bias, gamma, beta, out):
     rows, hidden = x.shape
     _dtype_code(x)
@@ -162,6 +186,20 @@ def turbo_add_bias_layernorm_dt(x, residual, bias, gamma, beta, eps: float, out:
                                              _dev_ptr(gamma, "gamma"), _dev_ptr(beta, "beta"), rows, hidden,
                                              float(eps), _dev_ptr(out, "out"), _dtype_code(x), _stream_ptr(stream)),
            "turbo_add_bias_layernorm_dt")
+    return out
+
+
+def turbo_add_bias_layernorm_varlen(x, residual, bias, gamma, beta, lengths: torch.Tensor, eps: float, out: torch.Tensor,
+                                    stream=None) -> torch.Tensor:
+    """x, residual, out [B,S,hidden]; token rows s >= lengths[b] are padding: neither read nor written."""
+    B, S, hidden = x.shape
+    _layernorm_args(x.view(B * S, hidden), None if residual is None else residual.view(B * S, hidden), bias, gamma, beta,
+                    out.view(B * S, hidden))
+    _check(lib().turbo_add_bias_layernorm_varlen(_dev_ptr(x, "x"), _dev_ptr(residual, "residual"), _dev_ptr(bias, "bias"),
+                                                 _dev_ptr(gamma, "gamma"), _dev_ptr(beta, "beta"),
+                                                 _lengths_ptr(lengths, B, "lengths"), B, S, hidden, float(eps),
+                                                 _dev_ptr(out, "out"), _dtype_code(x), _stream_ptr(stream)),
+           "turbo_add_bias_layernorm_varlen")
     return out
 
 

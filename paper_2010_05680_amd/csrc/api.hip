@@ -64,8 +64,8 @@ turbo::LaunchCfg launch_cfg(int num_cus) {
     return lc;
 }
 
-int softmax_impl(void* scores, const void* mask, long long msb, long long msq, int B, int H, int Sq, int Sk,
-                 float scale, int dtype, void* stream) {
+int softmax_impl(void* scores, const void* mask, long long msb, long long msq, const int* q_lengths,
+                 const int* k_lengths, int B, int H, int Sq, int Sk, float scale, int dtype, void* stream) {
     if (scores == nullptr) return TURBO_ERR_NULL;
     const int es = elem_size_of(dtype);
     if (es == 0) return TURBO_ERR_DTYPE;
@@ -82,11 +82,20 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, i
         align_elems = min_ll(align_elems, stride_alignment(msb));
         align_elems = min_ll(align_elems, stride_alignment(msq));
     }
-    const turbo::Plan plan = turbo::make_plan(Sk, es, align_elems, n_rows, turbo::kSoftmaxLimits, g_ovr);
+    turbo::Overrides ovr = g_ovr;
+    if (k_lengths != nullptr) {
+        if (reinterpret_cast<uintptr_t>(k_lengths) % 4 != 0 || reinterpret_cast<uintptr_t>(q_lengths) % 4 != 0)
+            return TURBO_ERR_ALIGN;
+        ovr.no_full = 1;
+    }
+    const turbo::Plan plan = turbo::make_plan(Sk, es, align_elems, n_rows, turbo::kSoftmaxLimits, ovr);
+    if (k_lengths != nullptr && plan.path == turbo::kPathStream) return TURBO_ERR_SHAPE;
 
     turbo::SoftmaxArgs a;
     a.scores = scores;
     a.mask = mask;
+    a.k_lengths = k_lengths;
+    a.q_lengths = q_lengths;
     a.mask_stride_b = msb;
     a.mask_stride_q = msq;
     a.n_rows = (int)n_rows;
@@ -106,7 +115,8 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, i
 }
 
 int layernorm_impl(const void* x, const void* residual, const void* bias, const void* gamma, const void* beta,
-                   int rows, int hidden, float eps, void* out, int dtype, void* stream) {
+                   int rows, int hidden, float eps, void* out, int dtype, void* stream, const int* lengths = nullptr,
+                   int S = 1) {
     if (x == nullptr || gamma == nullptr || beta == nullptr || out == nullptr) return TURBO_ERR_NULL;
     const int es = elem_size_of(dtype);
     if (es == 0) return TURBO_ERR_DTYPE;
@@ -131,6 +141,9 @@ int layernorm_impl(const void* x, const void* residual, const void* bias, const 
     a.hidden = hidden;
     a.eps = eps;
     a.inv_hidden = 1.0f / (float)hidden;
+    a.lengths = lengths;
+    a.S = S;
+    a.div_s = turbo::make_fastdiv((unsigned)S);
 
     int num_cus = 0;
     if (int st = current_num_cus(&num_cus)) return st;
@@ -235,12 +248,18 @@ int turbo_merge_heads(const void* x, int B, int H, int S, int D, void* out, int 
 
 int turbo_masked_softmax(void* scores, const void* mask, int B, int H, int Sq, int Sk, float scale, int dtype,
                          void* stream) {
-    return softmax_impl(scores, mask, (long long)Sq * Sk, Sk, B, H, Sq, Sk, scale, dtype, stream);
+    return softmax_impl(scores, mask, (long long)Sq * Sk, Sk, nullptr, nullptr, B, H, Sq, Sk, scale, dtype, stream);
 }
 
 int turbo_masked_softmax_ex(void* scores, const void* mask, long long mask_stride_b, long long mask_stride_q, int B,
                             int H, int Sq, int Sk, float scale, int dtype, void* stream) {
-    return softmax_impl(scores, mask, mask_stride_b, mask_stride_q, B, H, Sq, Sk, scale, dtype, stream);
+    return softmax_impl(scores, mask, mask_stride_b, mask_stride_q, nullptr, nullptr, B, H, Sq, Sk, scale, dtype, stream);
+}
+
+int turbo_masked_softmax_varlen(void* scores, const int* q_lengths, const int* k_lengths, int B, int H, int Sq, int Sk,
+                                float scale, int dtype, void* stream) {
+    if (k_lengths == nullptr) return TURBO_ERR_NULL;
+    return softmax_impl(scores, nullptr, 0, 0, q_lengths, k_lengths, B, H, Sq, Sk, scale, dtype, stream);
 }
 
 int turbo_add_bias_layernorm(const void* x, const void* residual, const void* bias, const void* gamma,
@@ -252,6 +271,15 @@ int turbo_add_bias_layernorm_dt(const void* x, const void* residual, const void*
                                 const void* beta, int rows, int hidden, float eps, void* out, int dtype,
                                 void* stream) {
     return layernorm_impl(x, residual, bias, gamma, beta, rows, hidden, eps, out, dtype, stream);
+}
+
+int turbo_add_bias_layernorm_varlen(const void* x, const void* residual, const void* bias, const void* gamma,
+                                    const void* beta, const int* lengths, int B, int S, int hidden, float eps,
+                                    void* out, int dtype, void* stream) {
+    if (lengths == nullptr) return TURBO_ERR_NULL;
+    if (B <= 0 || S <= 0 || (long long)B * S > kMaxRows) return TURBO_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(lengths) % 4 != 0) return TURBO_ERR_ALIGN;
+    return layernorm_impl(x, residual, bias, gamma, beta, B * S, hidden, eps, out, dtype, stream, lengths, S);
 }
 
 const char* turbo_status_string(int status) {

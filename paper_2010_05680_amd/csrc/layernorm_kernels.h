@@ -35,7 +35,20 @@ struct LayerNormArgs {
     int hidden;
     float eps;
     float inv_hidden;
+    // Length-aware mode for zero-padded batches: rows are (b, s) with s < S; rows with s >= lengths[b] are
+    // padding and are neither read nor written.  lengths == nullptr: every row is processed.
+    const int* lengths;
+    int S;
+    FastDiv div_s;
 };
+
+// Whether `row` is a padding row in length-aware mode.
+__device__ __forceinline__ bool is_padding_row(const LayerNormArgs& a, int row) {
+    if (a.lengths == nullptr) return false;
+    const unsigned b = fastdiv((unsigned)row, a.div_s);
+    const int s = (int)((unsigned)row - b * (unsigned)a.S);
+    return s >= a.lengths[b];
+}
 
 constexpr int log2_c(int g) { return g <= 1 ? 0 : 1 + log2_c(g / 2); }
 
@@ -109,7 +122,7 @@ __device__ __forceinline__ void load_bias(const T* p, int col, float (&dst)[VEC]
 // Measured on MI355X, short-lived workgroups stream better here than
 // persistent ones that keep the parameters across tiles.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, bool RES, int MODE>
+template <typename T, int VEC, int G, int NV, bool RES, int MODE, bool VARLEN>
 __global__ __launch_bounds__(64 * kWaveFamilyWaves) void layernorm_wave_kernel(LayerNormArgs a, int n_tiles) {
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
@@ -137,12 +150,15 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void layernorm_wave_kernel(L
 
     Pack<T, VEC> xr[R][NV];
     Pack<T, VEC> rr[R][NV];
+    bool live[R];  // the row exists and is not padding: only live rows are stored
     auto issue_loads = [&](int tl) {
         const int row_base = tl * TILE_ROWS + wave * (R * GPW) + grp;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             int row = row_base + r * GPW;
-            int rowc = row < a.n_rows ? row : a.n_rows - 1;  // out-of-range rows recompute the last row, unstored
+            live[r] = row < a.n_rows;
+            if constexpr (VARLEN) live[r] = live[r] && !is_padding_row(a, row);
+            int rowc = live[r] ? row : (VARLEN ? 0 : a.n_rows - 1);  // other rows recompute a valid row, unstored
             const long long off = (long long)rowc * hidden;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -152,6 +168,15 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void layernorm_wave_kernel(L
             }
         }
     };
+    if constexpr (VARLEN) {  // a wavefront whose rows are all padding issues no memory traffic
+        bool any_row = false;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int row = tile * TILE_ROWS + wave * (R * GPW) + grp + r * GPW;
+            any_row = any_row || (row < a.n_rows && !is_padding_row(a, row));
+        }
+        if (__ballot(any_row) == 0) return;
+    }
     issue_loads(tile);
 
     float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
@@ -233,7 +258,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void layernorm_wave_kernel(L
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int col = (v * G + gl) * VEC;
-                if (row < a.n_rows && (FULL || col < hidden)) {
+                if (live[r] && (FULL || col < hidden)) {
                     const int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
                     float g[VEC], be[VEC];
                     if constexpr (PRELOAD) {
@@ -309,7 +334,12 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     const int hidden = a.hidden;
     const int bd = (int)blockDim.x;
 
-    int row = blockIdx.x;
+    // rows of this workgroup: blockIdx.x, + gridDim.x, ... without the padding rows of length-aware mode
+    auto next_live_row = [&](int rw) {
+        while (rw < a.n_rows && is_padding_row(a, rw)) rw += (int)gridDim.x;
+        return rw;
+    };
+    int row = next_live_row(blockIdx.x);
     if (row >= a.n_rows) return;
 
     Pack<T, VEC> xr[NV];
@@ -392,7 +422,7 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
         }
         merge_stats_step<1, kWave, 0, 1, 6>(mean, m2, w1, w2);
 
-        const int next = row + (int)gridDim.x;
+        const int next = next_live_row(row + (int)gridDim.x);
         const bool more = next < a.n_rows;
         if (more) issue_loads(next);  // the raw registers are dead: refill them before the barrier
 
@@ -452,7 +482,8 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
     merge_weights_step<1, kWave, 0, 6>(n_w, w1, w2);
 
     int slot = 0;
-    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
+        if (is_padding_row(a, row)) continue;  // uniform over the workgroup
         const long long off = (long long)row * hidden;
         float n_run = 0.f, mu_run = 0.f, q_run = 0.f;
         for (long long col = (long long)tid * VEC; col < hidden; col += step) {
@@ -503,6 +534,7 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
             }
             store_stream<T, VEC>(out + off + col, o);
         }
+        slot ^= 1;  // only rows that used the LDS slot advance it
     }
 }
 
@@ -511,11 +543,16 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
 // ---------------------------------------------------------------------------
 template <typename T, int VEC, int G, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    (void)lc;
     constexpr int R = rows_in_flight_c(NV, VEC, kLayerNormLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE>), dim3(n_tiles), dim3(64 * kWaveFamilyWaves), 0, s, a,
-                       n_tiles);
+    if (a.lengths != nullptr)
+        hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE, true>), dim3(n_tiles),
+                           dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
+    else
+        hipLaunchKernelGGL((layernorm_wave_kernel<T, VEC, G, NV, RES, MODE, false>), dim3(n_tiles),
+                           dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 

@@ -77,6 +77,8 @@ struct Overrides {
     int path = -1;
     int max_vec_bytes = -1;
     int grid_waves = -1;
+    int no_full = 0;    // 1: the call needs per-row bounds checks (per-request lengths), never the exact-tiling mode
+    int no_stream = 0;  // 1: the call cannot use the two-sweep family
 };
 
 inline int round_up_nv(int nv) {
@@ -211,6 +213,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         p.rows = 1;
     }
     p.full = 0;
+    if (ovr.no_full) return p;
     if (!p.under_aligned && path == kPathWave) p.full = (long long)p.lanes * p.nv * vec == row_len;
     if (!p.under_aligned && path == kPathBlock) p.full = 64ll * p.waves * p.nv * vec == row_len;
     return p;

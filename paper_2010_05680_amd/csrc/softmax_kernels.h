@@ -18,11 +18,21 @@
 namespace turbo {
 
 
+// How the keys of a row are restricted.
+//   kMaskNone     : not at all
+//   kMaskAdditive : an additive mask tensor is added to the scaled scores
+//   kMaskLengths  : per-request lengths: keys k >= k_len[b] get weight exactly 0 without being read, and rows
+//                   q >= q_len[b] are skipped altogether (the variable-length batches of Section 2.1, without
+//                   the cost of their zero padding)
+enum MaskKind { kMaskNone = 0, kMaskAdditive = 1, kMaskLengths = 2 };
+
 struct SoftmaxArgs {
     void* scores;
     const void* mask;
     long long mask_stride_b;
     long long mask_stride_q;
+    const int* k_lengths;  // kMaskLengths: [B] valid keys per request
+    const int* q_lengths;  // kMaskLengths: [B] valid query rows per request, or null = all rows
     int n_rows;      // B*H*Sq
     int Sq;
     int Sk;
@@ -48,6 +58,18 @@ constexpr int kStreamCap = 32;
 constexpr int rows_in_flight_c(int nv, int vec, int target) {
     int r = target / (nv * vec);
     return r >= 8 ? 8 : r >= 4 ? 4 : r >= 2 ? 2 : 1;
+}
+
+// kMaskLengths: number of valid keys of `row` (clamped to 0..Sk); 0 also for rows that are skipped.
+__device__ __forceinline__ int row_key_count(const SoftmaxArgs& a, int row) {
+    const unsigned b = fastdiv((unsigned)row, a.div_rows_per_batch);
+    int klen = a.k_lengths[b];
+    klen = klen < 0 ? 0 : (klen > a.Sk ? a.Sk : klen);
+    if (a.q_lengths != nullptr) {
+        const int q = (int)((unsigned)row - fastdiv((unsigned)row, a.div_sq) * (unsigned)a.Sq);
+        if (q >= a.q_lengths[b]) klen = 0;
+    }
+    return klen;
 }
 
 template <typename T, bool MASK>
@@ -84,10 +106,13 @@ __device__ __forceinline__ int vec_overlap(int col, int row_len) {
 // Lane `gl` of a group holds vectors gl, gl+G, gl+2G, ... of its row, so one load
 // instruction of a wavefront covers 64/G consecutive rows in 16*G-byte pieces.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
+template <typename T, int VEC, int G, int NV, int MK, int MODE>
 __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
+    constexpr bool MASK = MK == kMaskAdditive;
+    constexpr bool VARLEN = MK == kMaskLengths;
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
+    static_assert(!(VARLEN && FULL), "per-row key counts need the bounds checks");
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int GPW = kWave / G;  // lane groups per wavefront
     constexpr int kWaves = kWaveFamilyWaves;
@@ -106,16 +131,34 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
 
         Pack<T, VEC> raw[R][NV];
         Pack<T, VEC> mraw[R][NV];
+        int klen[R];  // kMaskLengths: valid keys of the row, 0 = skip the row
+        if constexpr (VARLEN) {
+            bool any_row = false;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                int row = row_base + r * GPW;
+                klen[r] = row < a.n_rows ? row_key_count(a, row) : 0;
+                any_row = any_row || klen[r] > 0;
+            }
+            if (__ballot(any_row) == 0) continue;  // a wavefront whose rows are all padding issues no memory traffic
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             int row = row_base + r * GPW;
             int rowc = row < a.n_rows ? row : a.n_rows - 1;  // out-of-range rows recompute the last row, unstored
             const T* rp = scores + (long long)rowc * Sk;
             const T* mp = mask_row_ptr<T, MASK>(a, rowc);
+            if constexpr (!VARLEN) klen[r] = Sk;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int colc = FULL ? (v * G + gl) * VEC : vec_start<VEC, UA>((v * G + gl) * VEC, Sk);
-                raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
+                if constexpr (VARLEN) {
+                    // vectors that hold no valid key are not fetched: they re-read the first bytes of the tensor
+                    const bool needed = (v * G + gl) * VEC < Sk && colc < klen[r];
+                    raw[r][v] = load_stream<T, VEC, UA>(needed ? rp + colc : scores);
+                } else {
+                    raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
+                }
                 if constexpr (MASK) mraw[r][v] = load_pack<T, VEC, UA>(mp + colc);
             }
         }
@@ -128,6 +171,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const bool ok = FULL || (v * G + gl) * VEC < Sk;
+                const int c0 = VARLEN ? vec_start<VEC, UA>((v * G + gl) * VEC, Sk) : 0;  // column of element 0
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     float s = (float)raw[r][v].v[j];
@@ -136,7 +180,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
                         t = fmaf(s, scale, (float)mraw[r][v].v[j]);
                     else
                         t = s * scale;
-                    t = ok ? t : -INFINITY;
+                    t = (ok && (!VARLEN || c0 + j < klen[r])) ? t : -INFINITY;
                     z[r][v][j] = t;
                     m[r] = fmaxf(m[r], t);
                 }
@@ -147,7 +191,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
         float l[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float shift = -m[r] * kLog2e;
+            const float shift = (VARLEN && klen[r] == 0) ? 0.f : -m[r] * kLog2e;  // a skipped row has no maximum
             l[r] = 0.f;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -170,8 +214,8 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 int col = (v * G + gl) * VEC;
-                if (row < a.n_rows && (FULL || col < Sk)) {
-                    Pack<T, VEC> o;
+                if (row < a.n_rows && (FULL || col < Sk) && (!VARLEN || klen[r] > 0)) {
+                    Pack<T, VEC> o;  // keys past the row's count hold exp2(-inf) = 0
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
                     store_stream<T, VEC, UA>(rp + (FULL ? col : vec_start<VEC, UA>(col, Sk)), o);
@@ -208,10 +252,13 @@ __device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot
 }
 
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
-template <typename T, int VEC, int NV, bool MASK, int MODE>
+template <typename T, int VEC, int NV, int MK, int MODE>
 __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
+    constexpr bool MASK = MK == kMaskAdditive;
+    constexpr bool VARLEN = MK == kMaskLengths;
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
+    static_assert(!(VARLEN && FULL), "per-row key counts need the bounds checks");
     __shared__ SoftmaxLds lds;
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int tid = threadIdx.x;
@@ -222,16 +269,26 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
     const float scale = a.scale;
 
     int slot = 0;
-    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
         T* rp = scores + (long long)row * Sk;
         const T* mp = mask_row_ptr<T, MASK>(a, row);
+        int klen = Sk;
+        if constexpr (VARLEN) {
+            klen = row_key_count(a, row);
+            if (klen == 0) continue;  // the whole workgroup skips the row together
+        }
 
         Pack<T, VEC> raw[NV];
         Pack<T, VEC> mraw[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int colc = FULL ? (v * (int)blockDim.x + tid) * VEC : vec_start<VEC, UA>((v * (int)blockDim.x + tid) * VEC, Sk);
-            raw[v] = load_stream<T, VEC, UA>(rp + colc);
+            if constexpr (VARLEN) {
+                const bool needed = (v * (int)blockDim.x + tid) * VEC < Sk && colc < klen;
+                raw[v] = load_stream<T, VEC, UA>(needed ? rp + colc : scores);
+            } else {
+                raw[v] = load_stream<T, VEC, UA>(rp + colc);
+            }
             if constexpr (MASK) mraw[v] = load_pack<T, VEC, UA>(mp + colc);
         }
 
@@ -240,6 +297,7 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const bool ok = FULL || (v * (int)blockDim.x + tid) * VEC < Sk;
+            const int c0 = VARLEN ? vec_start<VEC, UA>((v * (int)blockDim.x + tid) * VEC, Sk) : 0;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
                 float s = (float)raw[v].v[j];
@@ -248,7 +306,7 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
                     t = fmaf(s, scale, (float)mraw[v].v[j]);
                 else
                     t = s * scale;
-                t = ok ? t : -INFINITY;
+                t = (ok && (!VARLEN || c0 + j < klen)) ? t : -INFINITY;
                 z[v][j] = t;
                 m[0] = fmaxf(m[0], t);
             }
@@ -282,6 +340,7 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
                 store_stream<T, VEC, UA>(rp + (FULL ? col : vec_start<VEC, UA>(col, Sk)), o);
             }
         }
+        slot ^= 1;  // only rows that used the LDS slot advance it (skipped rows execute no barrier)
     }
 }
 
@@ -376,82 +435,88 @@ inline int capped_grid(long long work_items, int waves_per_block, int default_ca
     return (int)(g < 1 ? 1 : g);
 }
 
-template <typename T, int VEC, int G, int NV, bool MASK, int MODE>
+template <typename T, int VEC, int G, int NV, int MK, int MODE>
 hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MASK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
+    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
                        dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, int NV, bool MASK, int MODE>
+template <typename T, int VEC, int NV, int MK, int MODE>
 hipError_t launch_softmax_block(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MASK, MODE>),
+    hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MK, MODE>),
                        dim3(capped_grid(a.n_rows, p.waves, kSoftmaxBlockCap, lc)), dim3(64 * p.waves), 0, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VEC, bool MASK, int MODE>
+template <typename T, int VEC, int MK, int MODE>
 hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     if (p.path == kPathWave) {
         if (p.lanes < 64) {
             if (p.nv == 1) {
                 switch (p.lanes) {
-                    case 4: return launch_softmax_wave<T, VEC, 4, 1, MASK, MODE>(a, lc, s);
-                    case 8: return launch_softmax_wave<T, VEC, 8, 1, MASK, MODE>(a, lc, s);
-                    case 16: return launch_softmax_wave<T, VEC, 16, 1, MASK, MODE>(a, lc, s);
-                    case 32: return launch_softmax_wave<T, VEC, 32, 1, MASK, MODE>(a, lc, s);
+                    case 4: return launch_softmax_wave<T, VEC, 4, 1, MK, MODE>(a, lc, s);
+                    case 8: return launch_softmax_wave<T, VEC, 8, 1, MK, MODE>(a, lc, s);
+                    case 16: return launch_softmax_wave<T, VEC, 16, 1, MK, MODE>(a, lc, s);
+                    case 32: return launch_softmax_wave<T, VEC, 32, 1, MK, MODE>(a, lc, s);
                 }
             } else if constexpr (MODE == kModeFull) {  // narrower groups with several vectors only when they tile the row
-                if (p.lanes == 32 && p.nv == 3) return launch_softmax_wave<T, VEC, 32, 3, MASK, MODE>(a, lc, s);
+                if (p.lanes == 32 && p.nv == 3) return launch_softmax_wave<T, VEC, 32, 3, MK, MODE>(a, lc, s);
                 if constexpr (5 * VEC <= kSoftmaxLimits.wave_max_epl)
-                    if (p.lanes == 32 && p.nv == 5) return launch_softmax_wave<T, VEC, 32, 5, MASK, MODE>(a, lc, s);
-                if (p.lanes == 16 && p.nv == 3) return launch_softmax_wave<T, VEC, 16, 3, MASK, MODE>(a, lc, s);
+                    if (p.lanes == 32 && p.nv == 5) return launch_softmax_wave<T, VEC, 32, 5, MK, MODE>(a, lc, s);
+                if (p.lanes == 16 && p.nv == 3) return launch_softmax_wave<T, VEC, 16, 3, MK, MODE>(a, lc, s);
             }
             return hipErrorInvalidValue;
         }
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 1, MASK, MODE>(a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 2, MASK, MODE>(a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 3, MASK, MODE>(a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 4, MASK, MODE>(a, lc, s); else break;
-            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 5, MASK, MODE>(a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 6, MASK, MODE>(a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 8, MASK, MODE>(a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 12, MASK, MODE>(a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 16, MASK, MODE>(a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 1, MK, MODE>(a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 2, MK, MODE>(a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 3, MK, MODE>(a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 4, MK, MODE>(a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 5, MK, MODE>(a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 6, MK, MODE>(a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 8, MK, MODE>(a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 12, MK, MODE>(a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.wave_max_epl) return launch_softmax_wave<T, VEC, 64, 16, MK, MODE>(a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
     if (p.path == kPathBlock) {
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MASK, MODE>(p, a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MASK, MODE>(p, a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MASK, MODE>(p, a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MASK, MODE>(p, a, lc, s); else break;
-            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.block_max_epl) return launch_softmax_block<T, VEC, 5, MASK, MODE>(p, a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MASK, MODE>(p, a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MASK, MODE>(p, a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MASK, MODE>(p, a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MASK, MODE>(p, a, lc, s); else break;
+            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MK, MODE>(p, a, lc, s); else break;
+            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MK, MODE>(p, a, lc, s); else break;
+            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MK, MODE>(p, a, lc, s); else break;
+            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MK, MODE>(p, a, lc, s); else break;
+            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.block_max_epl) return launch_softmax_block<T, VEC, 5, MK, MODE>(p, a, lc, s); else break;
+            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MK, MODE>(p, a, lc, s); else break;
+            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MK, MODE>(p, a, lc, s); else break;
+            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MK, MODE>(p, a, lc, s); else break;
+            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MK, MODE>(p, a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }
-    hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MASK>),
-                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
-    return hipGetLastError();
+    if constexpr (MK == kMaskLengths) {
+        return hipErrorInvalidValue;  // the two-sweep kernels do not take per-request lengths
+    } else {
+        hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MK == kMaskAdditive>),
+                           dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
+        return hipGetLastError();
+    }
 }
 
 // UA_OK: the under-aligned flavour exists only for the widest vector of each element type.
-template <typename T, int VEC, bool MASK, bool UA_OK>
+template <typename T, int VEC, int MK, bool UA_OK>
 hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     switch (row_mode(p)) {
-        case kModeFull: return launch_softmax_vm<T, VEC, MASK, kModeFull>(p, a, lc, s);
-        case kModeRagged: return launch_softmax_vm<T, VEC, MASK, kModeRagged>(p, a, lc, s);
+        case kModeFull:
+            if constexpr (MK != kMaskLengths) return launch_softmax_vm<T, VEC, MK, kModeFull>(p, a, lc, s);
+            break;
+        case kModeRagged: return launch_softmax_vm<T, VEC, MK, kModeRagged>(p, a, lc, s);
         case kModeUnder:
-            if constexpr (UA_OK) return launch_softmax_vm<T, VEC, MASK, kModeUnder>(p, a, lc, s);
+            if constexpr (UA_OK) return launch_softmax_vm<T, VEC, MK, kModeUnder>(p, a, lc, s);
             break;
     }
     return hipErrorInvalidValue;
@@ -459,7 +524,9 @@ hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg
 
 template <typename T, int VEC, bool UA_OK = false>
 hipError_t launch_softmax_v(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    return a.mask ? launch_softmax_m<T, VEC, true, UA_OK>(p, a, lc, s) : launch_softmax_m<T, VEC, false, UA_OK>(p, a, lc, s);
+    if (a.k_lengths) return launch_softmax_m<T, VEC, kMaskLengths, UA_OK>(p, a, lc, s);
+    return a.mask ? launch_softmax_m<T, VEC, kMaskAdditive, UA_OK>(p, a, lc, s)
+                  : launch_softmax_m<T, VEC, kMaskNone, UA_OK>(p, a, lc, s);
 }
 
 // Defined once per element type in softmax_f32.hip / softmax_f16.hip.

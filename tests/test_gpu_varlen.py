@@ -1,0 +1,130 @@
+"""Parity of the length-aware variants (zero-padded variable-length batches) against the CPU oracle, and proof that
+padding is neither read into the result nor written."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turbo_oracle as orc
+from paper_2010_05680_amd import binding as tb
+from paper_2010_05680_amd import workloads as wl
+
+from conftest import assert_parity
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+F32, F16 = np.float32, np.float16
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _run_softmax(scores, q_len, k_len, scale):
+    s = gu.dev(scores)
+    ql = None if q_len is None else torch.from_numpy(np.asarray(q_len, dtype=np.int32)).cuda()
+    kl = torch.from_numpy(np.asarray(k_len, dtype=np.int32)).cuda()
+    tb.turbo_masked_softmax_varlen(s, ql, kl, scale)
+    torch.cuda.synchronize()
+    return s
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+@pytest.mark.parametrize("path", [-1, tb.PATH_WAVE, tb.PATH_BLOCK])
+def test_varlen_softmax_shapes(dtype, path):
+    rng = np.random.Generator(np.random.Philox(21))
+    for B, H, S in [(1, 1, 1), (3, 2, 7), (4, 3, 16), (5, 2, 33), (6, 2, 64), (4, 2, 100), (3, 2, 128), (4, 1, 257), (2, 1, 493),
+                    (2, 1, 1000), (1, 1, 2048), (2, 1, 4100)]:
+        scores = (rng.standard_normal((B, H, S, S), dtype=np.float32) * 3).astype(dtype)
+        lens = rng.integers(0, S + 1, size=B)
+        lens[0] = S                       # one request fills the batch, as the padded layout implies
+        if B > 1:
+            lens[1] = min(S, 1)
+        for q_len in (lens, None):
+            with gu.overrides(path=path):
+                got = _np(_run_softmax(scores, q_len, lens, 0.125))
+            want = orc.masked_softmax_varlen(scores, q_len, lens, 0.125)
+            assert_parity(got, want, dtype, f"varlen softmax B={B} H={H} S={S} path={path} q_len={'yes' if q_len is not None else 'no'}")
+            # padding rows must be bit-identical to the input (never written)
+            if q_len is not None:
+                for b in range(B):
+                    np.testing.assert_array_equal(got[b, :, lens[b]:, :], scores[b, :, lens[b]:, :])
+
+
+def test_varlen_softmax_ignores_what_lies_beyond_the_lengths():
+    """NaNs planted in every padded key and padded query row must not reach any real output."""
+    rng = np.random.Generator(np.random.Philox(22))
+    B, H, S = 6, 3, 200
+    lens = np.array([200, 5, 77, 128, 1, 199])
+    scores = (rng.standard_normal((B, H, S, S), dtype=np.float32) * 3)
+    poisoned = scores.copy()
+    for b, n in enumerate(lens):
+        poisoned[b, :, :, n:] = np.nan
+        poisoned[b, :, n:, :] = np.nan
+    got = _np(_run_softmax(poisoned, lens, lens, 0.125))
+    want = orc.masked_softmax_varlen(scores, lens, lens, 0.125)
+    for b, n in enumerate(lens):
+        assert_parity(got[b, :, :n, :], want[b, :, :n, :], F32, f"request {b}")
+        assert (got[b, :, :n, n:] == 0).all()
+
+
+def test_varlen_softmax_matches_the_padded_kernel_on_config_2():
+    spec = wl.config_spec(2)
+    case = wl.softmax_case(spec)
+    lens = spec.lengths.astype(np.int32)
+    padded = gu.run_softmax(case)
+    got = _run_softmax(case.scores, lens, lens, case.scale)
+    B, H, Sq, Sk = case.shape
+    rows = gu.sample_rows(B * H * Sq, 400, seed=3)
+    # oracle on the sampled rows: build per-row lengths through a [n,1,1,Sk] view (one "request" per row)
+    b_of = rows // (H * Sq)
+    q_of = rows % Sq
+    sub = case.scores.reshape(-1, Sk)[rows].reshape(len(rows), 1, 1, Sk)
+    k_len = lens[b_of]
+    q_len = (q_of < lens[b_of]).astype(np.int32)  # 1 row per pseudo-request: active iff 0 < q_len
+    want = orc.masked_softmax_varlen(sub, q_len, k_len, case.scale).reshape(len(rows), Sk)
+    got_rows = _np(got.view(-1, Sk)[torch.from_numpy(rows).cuda()])
+    assert_parity(got_rows, want, F32, "config 2 varlen, sampled rows")
+    # on real rows the two kernels agree with each other to rounding (identical zeros on the padding keys)
+    real = torch.from_numpy(np.repeat(np.arange(Sq)[None, :] < lens[:, None], H, axis=0).reshape(-1)).cuda()
+    a, b = got.view(-1, Sk)[real], padded.view(-1, Sk)[real]
+    assert (a - b).abs().max().item() < 2e-7
+    assert ((a == 0) == (b == 0)).all()
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+@pytest.mark.parametrize("path", [-1, tb.PATH_BLOCK, tb.PATH_STREAM])
+def test_varlen_layernorm(dtype, path):
+    rng = np.random.Generator(np.random.Philox(23))
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    for B, S, hidden in [(1, 1, 8), (3, 5, 64), (4, 37, 768), (2, 9, 1000), (3, 7, 4096), (32, 50, 768)]:
+        x = rng.standard_normal((B, S, hidden), dtype=np.float32).astype(dtype)
+        r = rng.standard_normal((B, S, hidden), dtype=np.float32).astype(dtype)
+        bias, gamma, beta = (rng.standard_normal((hidden,), dtype=np.float32).astype(dtype) for _ in range(3))
+        lens = rng.integers(0, S + 1, size=B).astype(np.int32)
+        lens[0] = S
+        # poison the padding of the inputs and mark the padding of the output
+        xp, rp = x.copy(), r.copy()
+        for b, n in enumerate(lens):
+            xp[b, n:] = np.nan
+            rp[b, n:] = np.nan
+        out = torch.full((B, S, hidden), -7.25, dtype=tdt, device="cuda")
+        with gu.overrides(path=path):
+            tb.turbo_add_bias_layernorm_varlen(gu.dev(xp), gu.dev(rp), gu.dev(bias), gu.dev(gamma), gu.dev(beta),
+                                               torch.from_numpy(lens).cuda(), 1e-5, out)
+            torch.cuda.synchronize()
+        want = orc.add_bias_layernorm_varlen(x, r, bias, gamma, beta, lens, 1e-5, np.full((B, S, hidden), -7.25))
+        assert_parity(_np(out), want, dtype, f"varlen layernorm B={B} S={S} hidden={hidden} path={path}")
+        for b, n in enumerate(lens):
+            assert (_np(out[b, n:]) == -7.25).all(), "a padding row was written"
+
+
+def test_varlen_error_paths():
+    L = tb.lib()
+    fake = 0x10000
+    assert L.turbo_masked_softmax_varlen(fake, None, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert L.turbo_masked_softmax_varlen(fake, None, fake + 2, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert L.turbo_masked_softmax_varlen(fake, None, fake, 1, 1, 4, 70000, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_add_bias_layernorm_varlen(fake, fake, fake, fake, fake, None, 1, 4, 8, 1e-5, fake, tb.TURBO_F32, None) \
+        == tb.TURBO_ERR_NULL
+    assert L.turbo_add_bias_layernorm_varlen(fake, fake, fake, fake, fake, fake, 0, 4, 8, 1e-5, fake, tb.TURBO_F32, None) \
+        == tb.TURBO_ERR_SHAPE

@@ -42,6 +42,10 @@ MUTATIONS = [
     ("split_source_order", "((((long long)b * S + s) * n_split + k) * H + h) * D + d;", "((((long long)b * S + s) * H + h) * n_split + k) * D + d;"),
     ("split_dest_heads_and_sequence_swapped", "((((long long)k * B + b) * H + h) * S + s) * D + d;", "((((long long)k * B + b) * S + s) * H + h) * D + d;"),
     ("split_bias_ignores_split_index", "bias[((long long)k * H + h) * D + d]", "bias[((long long)h) * D + d]"),
+    ("varlen_softmax_reads_one_key_too_many", "for (int k = 0; k < kl; ++k) {\n                    y[k] = exp(scale * s[k] - m);", "for (int k = 0; k <= kl && k < Sk; ++k) {\n                    y[k] = exp(scale * s[k] - m);"),
+    ("varlen_softmax_tail_not_zeroed", "for (int k = kl; k < Sk; ++k) y[k] = 0.0;", "for (int k = kl; k < Sk; ++k) y[k] = s[k];"),
+    ("varlen_softmax_ignores_query_lengths", "int active = kl > 0 && (q_len == NULL || q < q_len[b]);", "int active = kl > 0;"),
+    ("varlen_layernorm_off_by_one_row", "if (s < len[b])\n                oracle_add_bias_layernorm(", "if (s <= len[b])\n                oracle_add_bias_layernorm("),
     ("merge_is_a_copy", "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];",
      "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * S + s) * H + h) * D + d];"),
 ]
@@ -58,7 +62,8 @@ def test_pins_catch_planted_mistake(tmp_path, name, old, new):
                            str(mutated), "-lm"])
     env = dict(os.environ, TURBO_ORACLE_LIB=str(lib))
     res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                          os.path.join(ROOT, "tests", "test_oracle_pins_elementwise.py"), "-x", "-q",
+                          os.path.join(ROOT, "tests", "test_oracle_pins_elementwise.py"),
+                          os.path.join(ROOT, "tests", "test_oracle_pins_varlen.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True)
     assert res.returncode != 0, f"the pins did not notice the planted mistake '{name}'"
     assert "failed" in res.stdout or "error" in res.stdout.lower()

@@ -1,0 +1,57 @@
+"""Pins for the oracle's length-aware variants (zero-padded variable-length batches)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turbo_oracle as orc
+from paper_2010_05680_amd import workloads as wl
+
+
+def test_varlen_softmax_by_hand():
+    # one request, 4 keys of which 3 are real: the weights of logs of 1, 2, 3 and an exact zero; second query row is padding
+    s = np.array([[0.0, 8 * np.log(2), 8 * np.log(3), 123.0], [5.0, 6.0, 7.0, 8.0]]).reshape(1, 1, 2, 4)
+    y = orc.masked_softmax_varlen(s, [1], [3], 0.125)
+    np.testing.assert_allclose(y[0, 0, 0], [1 / 6, 1 / 3, 1 / 2, 0.0], rtol=1e-14)
+    assert y[0, 0, 0, 3] == 0.0
+    np.testing.assert_array_equal(y[0, 0, 1], [5.0, 6.0, 7.0, 8.0])  # untouched
+    # no query lengths: every row is computed
+    y = orc.masked_softmax_varlen(s, None, [3], 0.125)
+    assert y[0, 0, 1, 3] == 0.0 and y[0, 0, 1, :3].sum() == pytest.approx(1.0)
+    # a request without keys is left alone
+    np.testing.assert_array_equal(orc.masked_softmax_varlen(s, None, [0], 0.125), s)
+
+
+def test_varlen_softmax_equals_library_softmax_on_the_real_part():
+    rng = np.random.default_rng(0)
+    B, H, S = 4, 3, 9
+    s = rng.normal(size=(B, H, S, S)) * 3
+    lens = np.array([9, 1, 5, 7])
+    y = orc.masked_softmax_varlen(s, lens, lens, 0.3)
+    for b, n in enumerate(lens):
+        want = torch.softmax(torch.from_numpy(s[b, :, :n, :n]) * 0.3, -1).numpy()
+        np.testing.assert_allclose(y[b, :, :n, :n], want, rtol=1e-13)
+        assert (y[b, :, :n, n:] == 0).all()
+        np.testing.assert_array_equal(y[b, :, n:, :], s[b, :, n:, :])
+
+
+def test_varlen_softmax_agrees_with_the_padded_formulation_on_real_rows():
+    """The additive 0 / -10000 key mask of the padded batch gives the same weights: exp underflows to the same zeros."""
+    case = wl.random_softmax_case(5, 3, 2, 12, 12, mask_kind="key")
+    padded = orc.masked_softmax(case.scores, case.mask, case.mask_stride_b, case.mask_stride_q, case.scale)
+    y = orc.masked_softmax_varlen(case.scores, None, case.lengths, case.scale)
+    np.testing.assert_allclose(y, padded, rtol=1e-13, atol=0)
+
+
+def test_varlen_layernorm_touches_only_real_rows():
+    rng = np.random.default_rng(1)
+    B, S, hidden = 3, 6, 16
+    x, r = rng.normal(size=(B, S, hidden)), rng.normal(size=(B, S, hidden))
+    b, g, be = rng.normal(size=hidden), rng.normal(size=hidden), rng.normal(size=hidden)
+    before = np.full((B, S, hidden), -7.25)
+    lens = [6, 0, 2]
+    y = orc.add_bias_layernorm_varlen(x, r, b, g, be, lens, 1e-5, before)
+    T = torch.from_numpy
+    want = torch.nn.functional.layer_norm(T(x) + T(b) + T(r), (hidden,), T(g), T(be), 1e-5).numpy()
+    for bi, n in enumerate(lens):
+        np.testing.assert_allclose(y[bi, :n], want[bi, :n], rtol=1e-11, atol=1e-13)
+        assert (y[bi, n:] == -7.25).all()
