@@ -322,3 +322,37 @@ def test_non_default_stream_and_repeat_calls():
     # softmax of a softmax output is a valid input too: the call is repeatable on its own output
     again = wl.SoftmaxCase(_np(got_s), None, 0, 0, 1.0, "none")
     assert_parity(_np(gu.run_softmax(again)), gu.oracle_softmax(again), F32, "softmax applied twice")
+
+
+def test_hip_graph_capture_and_replay():
+    """The library allocates nothing and never synchronises, so its launches can be captured into a HIP graph.
+    Every replay is checked against the eager result, with eager work and synchronisations in between."""
+    spec = wl.config_spec(1)
+    sc, lc = wl.softmax_case(spec), wl.layernorm_case(spec)
+    st = torch.cuda.Stream()
+    src = gu.dev(sc.scores)
+    work = torch.empty_like(src)
+    x, r = gu.dev(lc.x), gu.dev(lc.residual)
+    b, g, be = gu.dev(lc.bias), gu.dev(lc.gamma), gu.dev(lc.beta)
+    out = torch.empty_like(x)
+    want_s, want_l = gu.oracle_softmax(sc), gu.oracle_layernorm(lc)
+    with torch.cuda.stream(st):
+        work.copy_(src)
+        tb.turbo_masked_softmax(work, None, sc.scale, stream=st)       # eager reference run (also warms up)
+        tb.turbo_add_bias_layernorm(x, r, b, g, be, lc.eps, out, stream=st)
+        st.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            work.copy_(src)
+            tb.turbo_masked_softmax(work, None, sc.scale, stream=st)
+            tb.turbo_add_bias_layernorm(x, r, b, g, be, lc.eps, out, stream=st)
+        for replay in range(4):
+            work.fill_(float("nan"))
+            out.fill_(float("nan"))
+            st.synchronize()
+            graph.replay()
+            st.synchronize()
+            assert_parity(_np(work), want_s, F32, f"softmax, graph replay {replay}")
+            assert_parity(_np(out), want_l, F32, f"layernorm, graph replay {replay}")
+            tb.turbo_add_bias_layernorm(x, r, b, g, be, lc.eps, out, stream=st)  # eager work between replays
+            st.synchronize()
