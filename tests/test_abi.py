@@ -141,3 +141,49 @@ def test_plan_families_follow_row_length():
     assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave")
     with pytest.raises(tb.TurboError):
         tb.turbo_set_override(99, 0)
+
+
+def _parse_plan(text):
+    fam, rest = text.split(" ", 1)
+    kv = dict(item.split("=") for item in rest.split())
+    vec = kv["vec"]
+    mode = "u" if vec.endswith("u") else "f" if vec.endswith("f") else "r"
+    return fam, int(vec.rstrip("uf")), mode, {k: int(v) for k, v in kv.items() if k != "vec"}
+
+
+def test_planner_invariants_over_many_shapes():
+    """Whatever the shape, the chosen variant must be one that is compiled and must cover the row: the kernels trust
+    the plan, so a plan outside these bounds would mean wrong results or reads outside the row."""
+    rng = np.random.default_rng(7)
+    lens = list(range(1, 300)) + [int(v) for v in rng.integers(300, 70000, size=400)] + \
+        [512, 768, 1024, 1280, 1536, 2048, 2560, 3072, 4096, 5120, 8192, 16384, 32768, 32772, 65536, 100000]
+    supported_nv = {1, 2, 3, 4, 5, 6, 8, 12, 16}
+    for op, wave_max, block_max in ((0, 64, 32), (1, 24, 16)):
+        for dtype, es in ((tb.TURBO_F32, 4), (tb.TURBO_F16, 2)):
+            for L in lens:
+                for aligned in (True, False):
+                    for rows in (7, 100000):
+                        fam, vec, mode, kv = _parse_plan(tb.turbo_describe_plan(op, rows, L, dtype, aligned))
+                        what = f"op={op} dtype={dtype} L={L} aligned={aligned} rows={rows}: {fam} vec={vec}{mode} {kv}"
+                        assert vec in (1, 2, 4, 8) and vec * es <= 16, what
+                        if mode == "u":
+                            assert vec * es == 16 and L >= vec and (L % vec != 0 or not aligned), what
+                        else:
+                            assert L % vec == 0 and (aligned or vec == 1), what
+                        nvec = -(-L // vec)
+                        if fam == "wave":
+                            lanes, nv = kv["lanes"], kv["nv"]
+                            assert lanes in (4, 8, 16, 32, 64) and nv in supported_nv and kv["rows"] in (1, 2, 4, 8), what
+                            assert lanes * nv >= nvec and nv * vec <= wave_max, what
+                            if lanes < 64 and nv > 1:
+                                assert mode == "f" and (lanes, nv) in ((32, 3), (32, 5), (16, 3)), what
+                            if mode == "f":
+                                assert lanes * nv * vec == L, what
+                        elif fam == "block":
+                            w, nv = kv["waves"], kv["nv"]
+                            assert w in (2, 4, 8, 16) and nv in supported_nv, what
+                            assert 64 * w * nv >= nvec and (nv * vec <= block_max or nv == 1), what
+                            if mode == "f":
+                                assert 64 * w * nv * vec == L, what
+                        else:
+                            assert fam == "stream" and mode == "r", what
