@@ -223,6 +223,12 @@ int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, 
     a.div_n1 = turbo::make_fastdiv((unsigned)N1);
     a.div_b = turbo::make_fastdiv((unsigned)B);
     a.out_order = out_order;
+    // grouped kernel: the unrolled dimension (n2 when walking the output, n1 when walking the input) must divide
+    // evenly, and a bias is only supported when it does not depend on that dimension (input order)
+    const int unrolled = out_order ? N2 : N1;
+    a.grouped = unrolled % turbo::kElemUnroll == 0 && !(bias != nullptr && out_order) && g_ovr.path != 2;
+    a.div_n1u = turbo::make_fastdiv((unsigned)(N1 % turbo::kElemUnroll == 0 ? N1 / turbo::kElemUnroll : 1));
+    a.div_n2u = turbo::make_fastdiv((unsigned)(N2 % turbo::kElemUnroll == 0 ? N2 / turbo::kElemUnroll : 1));
     hipError_t err = turbo::launch_permute_heads(a, es, vec, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }

@@ -29,6 +29,19 @@ hipError_t gelu_tv(const GeluArgs& a, bool ua, hipStream_t s) {
 
 template <typename T, int VEC>
 hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
+    if (a.grouped) {
+        const long long items = a.total / (VEC * kElemUnroll);
+        const dim3 g((unsigned)((items + kElemThreads - 1) / kElemThreads)), blk(kElemThreads);
+        if (a.bias) {
+            // with a bias the unrolled dimension must not enter the bias index: true for the split (input order)
+            hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, true, false>), g, blk, 0, s, a);
+        } else if (a.out_order) {
+            hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, false, true>), g, blk, 0, s, a);
+        } else {
+            hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, false, false>), g, blk, 0, s, a);
+        }
+        return hipGetLastError();
+    }
     const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
     if (a.bias) {
         if (a.out_order)

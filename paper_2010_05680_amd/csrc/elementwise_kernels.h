@@ -128,6 +128,8 @@ struct PermuteArgs {
     long long total;   // B*N1*K*N2*D
     int B, N1, K, N2, D;
     FastDiv div_dv, div_n2, div_k, div_n1, div_b;  // D/VEC, N2, K, N1, B
+    FastDiv div_n1u, div_n2u;                      // N1/kElemUnroll, N2/kElemUnroll (grouped kernel)
+    int grouped;  // 1: use the grouped kernel (the unrolled dimension divides evenly)
     int out_order;  // 1: lanes walk the output tensor, 0: the input tensor
 };
 
@@ -189,6 +191,68 @@ __global__ __launch_bounds__(kElemThreads) void permute_heads_kernel(PermuteArgs
             for (int j = 0; j < VEC; ++j) o.v[j] = (T)((float)raw[u].v[j] + (float)pb.v[j]);
         }
         store_stream<T, VEC, false>(out + dst[u], o);
+    }
+}
+
+// Variant whose per-lane unroll runs along the dimension that is contiguous on the SCATTERED side of the copy:
+// a lane's kElemUnroll pieces are then adjacent there, so the scattered side moves kElemUnroll*D contiguous elements
+// per (lane group, unroll set) instead of D, while the other side stays fully coalesced per instruction.
+//   OUT_ORDER = false (split): lanes walk [b][n1/U][k][n2][dv], u runs over n1 (adjacent in the output);
+//   OUT_ORDER = true  (merge): lanes walk [k][b][n2/U][n1][dv], u runs over n2 (adjacent in the input).
+// Needs N1 (resp. N2) to be a multiple of kElemUnroll; the host falls back to the flat kernel otherwise.
+template <typename T, int VEC, bool BIAS, bool OUT_ORDER>
+__global__ __launch_bounds__(kElemThreads) void permute_heads_grouped_kernel(PermuteArgs a) {
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    T* out = reinterpret_cast<T*>(a.out);
+    const long long n_items = a.total / (VEC * kElemUnroll);
+    const long long i = (long long)blockIdx.x * kElemThreads + threadIdx.x;
+    if (i >= n_items) return;
+    unsigned rest = (unsigned)i;
+    unsigned q = fastdiv(rest, a.div_dv);
+    const unsigned dv = rest - q * a.div_dv.d;
+    rest = q;
+    unsigned b, n1, k, n2;
+    if constexpr (OUT_ORDER) {  // [k][b][n2/U][n1][dv]
+        q = fastdiv(rest, a.div_n1);
+        n1 = rest - q * a.div_n1.d;
+        rest = q;
+        q = fastdiv(rest, a.div_n2u);
+        n2 = (rest - q * a.div_n2u.d) * kElemUnroll;
+        rest = q;
+        q = fastdiv(rest, a.div_b);
+        b = rest - q * a.div_b.d;
+        k = q;
+    } else {  // [b][n1/U][k][n2][dv]
+        q = fastdiv(rest, a.div_n2);
+        n2 = rest - q * a.div_n2.d;
+        rest = q;
+        q = fastdiv(rest, a.div_k);
+        k = rest - q * a.div_k.d;
+        rest = q;
+        q = fastdiv(rest, a.div_n1u);
+        n1 = (rest - q * a.div_n1u.d) * kElemUnroll;
+        b = q;
+    }
+    const long long src0 = ((((long long)b * a.N1 + n1) * a.K + k) * a.N2 + n2) * a.D + (long long)dv * VEC;
+    const long long dst0 = ((((long long)k * a.B + b) * a.N2 + n2) * a.N1 + n1) * a.D + (long long)dv * VEC;
+    // stepping the unrolled dimension by one moves the source / destination by these many elements
+    const long long src_step = OUT_ORDER ? (long long)a.D : (long long)a.K * a.N2 * a.D;
+    const long long dst_step = OUT_ORDER ? (long long)a.N1 * a.D : (long long)a.D;
+    Pack<T, VEC> raw[kElemUnroll];
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) raw[u] = load_stream<T, VEC, false>(x + src0 + u * src_step);
+    Pack<T, VEC> pb;
+    if constexpr (BIAS) pb = load_pack<T, VEC, false>(bias + ((long long)k * a.N2 + n2) * a.D + (long long)dv * VEC);
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        Pack<T, VEC> o = raw[u];
+        if constexpr (BIAS) {
+            // in split order the bias index (k, n2, d) does not depend on the unrolled n1
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) o.v[j] = (T)((float)raw[u].v[j] + (float)pb.v[j]);
+        }
+        store_stream<T, VEC, false>(out + dst0 + u * dst_step, o);
     }
 }
 
