@@ -159,13 +159,14 @@ const char *turbo_status_string(int status);
  * they never change what is computed, only which kernel variant computes it.
  *
  * turbo_set_override(key, value): value < 0 restores the built-in choice.
- *   TURBO_OVR_PATH          force a kernel family: 0 wave (a group of lanes per
- *                           row), 1 block (a workgroup per row, LDS combine),
- *                           2 stream (a workgroup per row, row re-read from
- *                           memory).  A forced family that cannot hold the
- *                           row falls back to the built-in choice.
- *   TURBO_OVR_MAX_VEC_BYTES cap the width of one load/store (2..16 bytes)
- *   TURBO_OVR_GRID_WAVES    cap on resident workgroups per compute unit used to size the grid
+ *   TURBO_OVR_PATH          force a kernel family of the two reductions: 0 wave (a group of lanes per row),
+ *                           1 block (a workgroup per row, LDS combine), 2 stream (a workgroup per row, row
+ *                           re-read from memory).  A forced family that cannot hold the row falls back to the
+ *                           built-in choice.  For the head permutations, 2 selects the flat (ungrouped) kernel.
+ *   TURBO_OVR_MAX_VEC_BYTES cap the width of one load/store (2..16 bytes); any cap also selects the aligned
+ *                           narrow kernels instead of element-aligned 16-byte accesses for odd row lengths
+ *   TURBO_OVR_GRID_WAVES    cap on resident workgroups (of 4 wavefronts) per compute unit used to size the grid
+ *                           of the looping kernels
  * Returns TURBO_OK, or TURBO_ERR_SHAPE for an unknown key.
  *
  * turbo_describe_plan(op, rows, row_len, dtype, aligned16, buf, buf_len): writes

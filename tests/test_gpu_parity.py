@@ -356,3 +356,56 @@ def test_hip_graph_capture_and_replay():
             assert_parity(_np(out), want_l, F32, f"layernorm, graph replay {replay}")
             tb.turbo_add_bias_layernorm(x, r, b, g, be, lc.eps, out, stream=st)  # eager work between replays
             st.synchronize()
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_randomized_shapes_alignments_and_variants(chunk):
+    """Seeded sweep over shapes, element types, mask layouts, pointer offsets and forced kernel variants."""
+    rng = np.random.default_rng(9000 + chunk)
+    special = [1, 2, 3, 4, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 768, 1000,
+               1023, 1024, 1025, 1536, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 5000, 8191, 8192]
+    for case_no in range(60):
+        dtype = F32 if rng.random() < 0.5 else F16
+        tdt = torch.float32 if dtype == F32 else torch.float16
+        L = int(rng.choice(special)) if rng.random() < 0.7 else int(rng.integers(1, 6000))
+        path = int(rng.choice([-1, -1, tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM]))
+        vec_bytes = int(rng.choice([-1, -1, -1, 2, 4, 8, 16]))
+        if vec_bytes != -1 and vec_bytes < np.dtype(dtype).itemsize:
+            vec_bytes = -1
+        grid = int(rng.choice([-1, -1, 1, 3]))
+        offset = int(rng.integers(0, 8))
+        seed = int(rng.integers(1 << 30))
+        what = f"chunk {chunk} case {case_no}: L={L} dtype={np.dtype(dtype).name} path={path} vec={vec_bytes} grid={grid} off={offset}"
+        if rng.random() < 0.5:
+            B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+            Sq = int(rng.integers(1, max(2, min(40, 60000 // (L * B * H) + 1))))
+            kind = str(rng.choice(["none", "key", "dense"] + (["causal"] if L <= 300 else [])))
+            if kind == "causal":
+                Sq = L
+            case = wl.random_softmax_case(seed, B, H, Sq, L, dtype=dtype, mask_kind=kind)
+            n = case.scores.size
+            buf = torch.full((n + 16,), float("nan"), dtype=tdt, device="cuda")
+            view = buf[offset:offset + n].view(case.scores.shape)
+            view.copy_(torch.from_numpy(case.scores))
+            mask = None if case.mask is None else gu.dev(case.mask)
+            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid):
+                tb.turbo_masked_softmax_ex(view, mask, case.mask_stride_b, case.mask_stride_q, case.scale)
+                torch.cuda.synchronize()
+            assert_parity(_np(view), gu.oracle_softmax(case), dtype, "softmax " + what)
+            assert torch.isnan(buf[:offset]).all() and torch.isnan(buf[offset + n:]).all(), "softmax guard band " + what
+        else:
+            if L == 1:
+                continue
+            rows = int(rng.integers(1, max(2, min(60, 120000 // L + 1))))
+            case = wl.random_layernorm_case(seed, rows, L, dtype=dtype, eps=1e-5)
+            n = case.x.size
+            obuf = torch.full((n + 16,), float("nan"), dtype=tdt, device="cuda")
+            out = obuf[offset:offset + n].view(rows, L)
+            use_res, use_bias = bool(rng.random() < 0.8), bool(rng.random() < 0.8)
+            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid):
+                tb.turbo_add_bias_layernorm_dt(gu.dev(case.x), gu.dev(case.residual) if use_res else None,
+                                               gu.dev(case.bias) if use_bias else None, gu.dev(case.gamma),
+                                               gu.dev(case.beta), case.eps, out)
+                torch.cuda.synchronize()
+            assert_parity(_np(out), gu.oracle_layernorm(case, residual=use_res, bias=use_bias), dtype, "layernorm " + what)
+            assert torch.isnan(obuf[:offset]).all() and torch.isnan(obuf[offset + n:]).all(), "layernorm guard band " + what
