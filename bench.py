@@ -318,33 +318,41 @@ def main():
     period = max(ks.n_sm_sets, ks.n_ln_sets)
     step_bytes = ks.softmax_bytes + ks.layernorm_bytes
 
-    # ---- headline: K whole steps, wall clock bracketed by synchronisation ----
+    # ---- headline: exactly K whole steps, wall clock bracketed by synchronisation ----
+    steps = args.steps
     with torch.cuda.stream(stream):
-        graph, mode = None, "eager"
+        graph, graph_rem, mode = None, None, "eager"
         for i in range(args.warmup):
             ks.step(i, stream)
         stream.synchronize()
+        reps, rem = divmod(steps, period)
         if args.launch == "graph":
-            try:
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph, stream=stream):
-                    for i in range(period):
-                        ks.step(i, stream)
+            try:  # one graph holds a full rotation over the buffer sets; a second one the remainder of K
+                if reps:
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=stream):
+                        for i in range(period):
+                            ks.step(i, stream)
+                if rem:
+                    graph_rem = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph_rem, stream=stream):
+                        for i in range(rem):
+                            ks.step(i, stream)
                 mode = "graph"
-                graph.replay()
+                for g in (graph, graph_rem):
+                    if g is not None:
+                        g.replay()
                 stream.synchronize()
             except Exception as exc:
                 print(f"[bench] graph capture failed ({exc!r}); eager launches", file=sys.stderr)
-                graph = None
-        steps = args.steps
-        if graph is not None:
-            reps = max(1, -(-steps // period))
-            steps = reps * period
+                graph, graph_rem, mode = None, None, "eager"
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        if graph is not None:
+        if mode == "graph":
             for _ in range(reps):
                 graph.replay()
+            if graph_rem is not None:
+                graph_rem.replay()
         else:
             for i in range(steps):
                 ks.step(i, stream)
