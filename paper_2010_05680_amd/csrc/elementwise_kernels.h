@@ -26,25 +26,39 @@ struct GeluArgs {
     FastDiv div_hv;      // hidden / VEC when that is exact
 };
 
-// t * Phi(t) with Phi(-|t|) = erfc(u)/2, u = |t|/sqrt 2, and a branch-free erfc:
-//   erfc(u) ~= exp(-u^2) * (c1 w + ... + c7 w^7),  w = 1/(1 + u/2)
-// (1.2e-6 relative on [0, 9.5]; the resulting binary32 gelu stays within 0.16 of the parity bound
-// max(1e-6, 1e-5 |gelu|) over t in [-9, 9]).  The constants are fitted by csrc/fit_gelu_erfc.py; the math
-// library's erfc is exact to a few ulp but its range branches make this kernel ALU-bound (measured: 30 % of the
-// HBM peak for binary16 storage instead of 70 %).
+// t * Phi(t) = max(t, 0) - u Phi(-u),  u = min(|t|, 8)  (8 Phi(-8) < 1e-14, so the clamp costs nothing and keeps
+// infinite t finite in the product), with a branch-free tail of the normal distribution:  Phi(-u) ~= 2^Q(u),  Q a polynomial.
+// log2 Phi(-u) is smooth and nearly quadratic, so Q needs degree 5 for binary16 outputs (the result stays within
+// 0.18 of the parity bound max(1e-6, 3e-3 |gelu|), rounding to binary16 included) and degree 8 for binary32 (0.04 of
+// max(1e-6, 1e-5 |gelu|)).  The constants are fitted by csrc/fit_gelu_phi.py.  The math library's erfc is exact to a
+// few ulp but its range branches make this kernel ALU-bound (measured: 30 % of the HBM peak for binary16 storage);
+// this form costs DEGREE + 3 vector instructions and one transcendental per element.
+template <int DEGREE>
+struct PhiTail;
+template <>
+struct PhiTail<5> {
+    static constexpr float c[6] = {-1.0000791549682617f,  -1.1497708559036255f, -0.4628004729747772f,
+                                   -0.04924162104725838f, 0.00613403832539916f, -0.0003528775996528566f};
+};
+template <>
+struct PhiTail<8> {
+    static constexpr float c[9] = {-0.999998927116394f,      -1.151122808456421f,    -0.45911481976509094f,
+                                   -0.052720002830028534f,   0.007343560457229614f,  -0.00033137266291305423f,
+                                   -0.00011122971045551822f, 2.443803532514721e-05f, -1.6398848856624682e-06f};
+};
+template <int DEGREE>
 __device__ __forceinline__ float gelu_erf(float t) {
-    // u/2 = |t| / (2 sqrt 2);  exp(-u^2) = exp2(t^2 * (-log2(e)/2));  the 1/2 of erfc/2 is folded into c_k
-    const float w = fast_rcp(fmaf(fabsf(t), 0.35355339059327376f, 1.0f));
-    float p = 0.5f * 0.08912515640258789f;
-    p = fmaf(p, w, 0.5f * -0.3599849343299866f);
-    p = fmaf(p, w, 0.5f * 0.39377784729003906f);
-    p = fmaf(p, w, 0.5f * 0.03465970978140831f);
-    p = fmaf(p, w, 0.5f * 0.282719224691391f);
-    p = fmaf(p, w, 0.5f * 0.2773537337779999f);
-    p = fmaf(p, w, 0.5f * 0.28234806656837463f);
-    const float half_erfc = (p * w) * fast_exp2((t * t) * (-0.5f * kLog2e));  // Phi(-|t|)
-    return t * (t < 0.f ? half_erfc : 1.0f - half_erfc);
+    const float u = fminf(fabsf(t), 8.0f);
+    float q = PhiTail<DEGREE>::c[DEGREE];
+#pragma unroll
+    for (int k = DEGREE - 1; k >= 0; --k) q = fmaf(q, u, PhiTail<DEGREE>::c[k]);
+    return fmaf(-u, fast_exp2(q), fmaxf(t, 0.f));  // u, not |t|: beyond the clamp the product is < 1e-14 either way
 }
+// degree by storage type: what the output's rounding can show
+template <typename T>
+struct GeluDegree {
+    static constexpr int value = sizeof(T) == 2 ? 5 : 8;
+};
 __device__ __forceinline__ float gelu_tanh(float t) {
     // 0.5 t (1 + tanh u) = t / (1 + exp(-2u)),  u = sqrt(2/pi) (t + 0.044715 t^3)
     const float u = 0.7978845608028654f * fmaf(0.044715f * t * t, t, t);
@@ -104,7 +118,7 @@ __global__ __launch_bounds__(kElemThreads) void add_bias_gelu_kernel(GeluArgs a)
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
             const float t = (float)raw[u].v[j] + b[j];
-            o.v[j] = (T)(APPROX ? gelu_tanh(t) : gelu_erf(t));
+            o.v[j] = (T)(APPROX ? gelu_tanh(t) : gelu_erf<GeluDegree<T>::value>(t));
         }
         store_stream<T, VEC, UA>(out + e, o);
     }
@@ -113,7 +127,7 @@ __global__ __launch_bounds__(kElemThreads) void add_bias_gelu_kernel(GeluArgs a)
         for (long long e = n_vec * VEC; e < a.total; ++e) {
             const int col = (int)(e % a.hidden);
             const float t = (float)x[e] + (bias ? (float)bias[col] : 0.f);
-            out[e] = (T)(APPROX ? gelu_tanh(t) : gelu_erf(t));
+            out[e] = (T)(APPROX ? gelu_tanh(t) : gelu_erf<GeluDegree<T>::value>(t));
         }
     }
 }

@@ -57,6 +57,29 @@ def test_gelu_wide_range_no_bias_in_place_and_narrow_kernel():
         assert_parity(_np(_gelu(x, b, False)), orc.add_bias_gelu(x, b), F32, "gelu 4-byte kernel")
 
 
+def test_gelu_every_binary16_input_and_a_dense_binary32_grid():
+    """The erf form's tail approximation is a fit: check it over its whole domain, not on random draws.
+
+    binary16: all 63488 finite inputs (outputs that overflow binary16 are excluded: the oracle has no infinity there);
+    binary32: two million points over [-12, 12], where every regime of the bound max(atol, rtol |gelu|) occurs.
+    The margin that comes out (worst error / bound) is asserted to stay below 1/2, so a drift in the constants
+    shows before it reaches the parity bound itself.
+    """
+    half = np.arange(65536, dtype=np.uint16).view(F16)
+    half = half[np.isfinite(half)]
+    half = half[np.abs(half.astype(np.float64)) < 65000]
+    n16 = half.size - half.size % 8
+    cases = [(half[:n16].reshape(-1, 8), F16, 3e-3), (np.linspace(-12, 12, 1 << 21, dtype=F32).reshape(-1, 4096), F32, 1e-5)]
+    for x, dtype, rtol in cases:
+        for approximate in (False, True):
+            got = _np(_gelu(x, None, approximate)).astype(np.float64)
+            want = orc.add_bias_gelu(x, None, approximate)
+            assert_parity(got, want, dtype, f"gelu whole domain {np.dtype(dtype).name} approximate={approximate}")
+            if not approximate and dtype == F32:
+                margin = (np.abs(got - want) / np.maximum(1e-6, rtol * np.abs(want))).max()
+                assert margin < 0.5, f"binary32 erf gelu uses {margin:.2f} of the parity bound"
+
+
 @pytest.mark.parametrize("dtype", [F32, F16])
 def test_gelu_unaligned_pointers_and_guard_bands(dtype):
     rng = np.random.Generator(np.random.Philox(13))
