@@ -176,11 +176,23 @@ const char *turbo_status_string(int status);
  *
  * turbo_debug_fastdiv(n, d): the library's multiply-shift division n / d as the
  * kernels compute it (host evaluation; n < 2^31, d >= 1), for host-side tests.
+ *
+ * turbo_stream_probe(in0, in1, out, n_bytes, stream): measurement aid, not part of
+ * the method: the plain stream that the kernels above are compared with.  Treats
+ * the DEVICE buffers as n_bytes/4 binary32 values and writes out = in0 + in1, or
+ * out = in0 when in1 is NULL, with the same access shape as the element-wise
+ * kernels (16-byte non-temporal accesses).  out == in0 with in1 == NULL is the
+ * one-read-one-write mix of the in-place softmax; two inputs and a separate
+ * output are the two-reads-one-write mix of add-bias-LayerNorm.  Pointers must be
+ * 16-byte aligned (TURBO_ERR_ALIGN) and n_bytes a positive multiple of 16
+ * (TURBO_ERR_SHAPE); out may equal in0 or in1 exactly, other overlap is undefined.
+ * Asynchronous on `stream`; allocates nothing.
  */
 enum turbo_override { TURBO_OVR_PATH = 0, TURBO_OVR_MAX_VEC_BYTES = 1, TURBO_OVR_GRID_WAVES = 2, TURBO_OVR_COUNT_ = 3 };
 int turbo_set_override(int key, int value);
 int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16, char *buf, int buf_len);
 unsigned turbo_debug_fastdiv(unsigned n, unsigned d);
+int turbo_stream_probe(const void *in0, const void *in1, void *out, long long n_bytes, void *stream);
 
 #ifdef __cplusplus
 }

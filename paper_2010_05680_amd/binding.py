@@ -29,6 +29,7 @@ EXPORTED_SYMBOLS = (
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
     "turbo_batch_schedule", "turbo_mem_plan",
     "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
+    "turbo_stream_probe",
 )
 
 _lib = None
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.turbo_describe_plan.argtypes = [i, i, i, i, i, ctypes.c_char_p, i]
         L.turbo_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
         L.turbo_debug_fastdiv.restype = ctypes.c_uint
+        L.turbo_stream_probe.argtypes = [vp, vp, vp, ctypes.c_longlong, vp]
+        L.turbo_stream_probe.restype = i
         _lib = L
     return _lib
 
@@ -236,6 +239,16 @@ def turbo_merge_heads(x: torch.Tensor, out: torch.Tensor, stream=None) -> torch.
         raise ValueError("out must be [B,S,H,D] in x's dtype")
     _check(lib().turbo_merge_heads(_dev_ptr(x, "x"), B, H, S, D, _dev_ptr(out, "out"), dt, _stream_ptr(stream)),
            "turbo_merge_heads")
+    return out
+
+
+def turbo_stream_probe(in0: torch.Tensor, in1: Optional[torch.Tensor], out: torch.Tensor, stream=None) -> torch.Tensor:
+    """Measurement aid: out = in0 (+ in1) over the tensors' raw bytes taken as binary32 (same byte counts required)."""
+    n_bytes = in0.numel() * in0.element_size()
+    if out.numel() * out.element_size() != n_bytes or (in1 is not None and in1.numel() * in1.element_size() != n_bytes):
+        raise ValueError("all buffers must hold the same number of bytes")
+    _check(lib().turbo_stream_probe(_dev_ptr(in0, "in0"), _dev_ptr(in1, "in1"), _dev_ptr(out, "out"), n_bytes,
+                                    _stream_ptr(stream)), "turbo_stream_probe")
     return out
 
 

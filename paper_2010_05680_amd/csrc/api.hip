@@ -320,6 +320,17 @@ int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16,
     return TURBO_OK;
 }
 
+int turbo_stream_probe(const void* in0, const void* in1, void* out, long long n_bytes, void* stream) {
+    if (in0 == nullptr || out == nullptr) return TURBO_ERR_NULL;
+    // whole 16-byte vectors only; the workgroup count (1024 vectors each) must fit a 31-bit grid
+    if (n_bytes <= 0 || n_bytes % 16 != 0 || n_bytes / 16 / 1024 > 0x7FFFFFF0ll) return TURBO_ERR_SHAPE;
+    const uintptr_t bits = (uintptr_t)in0 | (uintptr_t)out | (uintptr_t)in1;
+    if (bits % 16 != 0) return TURBO_ERR_ALIGN;
+    const hipError_t e = turbo::launch_stream_probe((const float*)in0, (const float*)in1, (float*)out, n_bytes / 16,
+                                                    (hipStream_t)stream);
+    return e == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
+}
+
 unsigned turbo_debug_fastdiv(unsigned n, unsigned d) {
     if (d == 0) return 0;
     return turbo::fastdiv(n, turbo::make_fastdiv(d));

@@ -70,6 +70,15 @@ hipError_t launch_add_bias_gelu(const GeluArgs& a, int elem_size, int vec, bool 
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_stream_probe(const float* in0, const float* in1, float* out, long long n_vec, hipStream_t s) {
+    const dim3 grid(grid_for(n_vec)), block(kElemThreads);
+    if (in1)
+        hipLaunchKernelGGL((stream_probe_kernel<true>), grid, block, 0, s, in0, in1, out, n_vec);
+    else
+        hipLaunchKernelGGL((stream_probe_kernel<false>), grid, block, 0, s, in0, in1, out, n_vec);
+    return hipGetLastError();
+}
+
 hipError_t launch_permute_heads(const PermuteArgs& a, int elem_size, int vec, hipStream_t s) {
     if (elem_size == 4) {
         switch (vec) {

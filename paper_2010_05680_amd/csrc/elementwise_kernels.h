@@ -270,7 +270,36 @@ __global__ __launch_bounds__(kElemThreads) void permute_heads_grouped_kernel(Per
     }
 }
 
+// Measurement aid: the plain stream the fused kernels are compared with.  out = in0 (+ in1), binary32, same access
+// shape as the kernels above (16-byte non-temporal accesses, kElemUnroll vectors per lane, loads first).  With
+// out == in0 and no in1 it is the 1:1 read/write mix of the in-place softmax; with two inputs and a separate output
+// the 2:1 mix of add-bias-LayerNorm.
+template <bool TWO>
+__global__ __launch_bounds__(kElemThreads) void stream_probe_kernel(const float* in0, const float* in1, float* out,
+                                                                    long long n_vec) {
+    const long long base = (long long)blockIdx.x * (kElemThreads * kElemUnroll) + threadIdx.x;
+    Pack<float, 4> a[kElemUnroll], b[kElemUnroll];
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        const long long i = base + (long long)u * kElemThreads;
+        const long long ic = i < n_vec ? i : 0;
+        a[u] = load_stream<float, 4, false>(in0 + ic * 4);
+        if constexpr (TWO) b[u] = load_stream<float, 4, false>(in1 + ic * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < kElemUnroll; ++u) {
+        const long long i = base + (long long)u * kElemThreads;
+        if (i >= n_vec) continue;
+        if constexpr (TWO) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[u].v[j] += b[u].v[j];
+        }
+        store_stream<float, 4, false>(out + i * 4, a[u]);
+    }
+}
+
 hipError_t launch_add_bias_gelu(const GeluArgs& a, int elem_size, int vec, bool under_aligned, hipStream_t s);
+hipError_t launch_stream_probe(const float* in0, const float* in1, float* out, long long n_vec, hipStream_t s);
 hipError_t launch_permute_heads(const PermuteArgs& a, int elem_size, int vec, hipStream_t s);
 
 }  // namespace turbo

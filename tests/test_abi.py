@@ -187,3 +187,14 @@ def test_planner_invariants_over_many_shapes():
                                 assert 64 * w * nv * vec == L, what
                         else:
                             assert fam == "stream" and mode == "r", what
+
+
+def test_stream_probe_rejects_bad_arguments_without_a_gpu():
+    L = tb.lib()
+    fake = 0x10000
+    assert L.turbo_stream_probe(None, None, fake, 64, None) == tb.TURBO_ERR_NULL
+    assert L.turbo_stream_probe(fake, None, None, 64, None) == tb.TURBO_ERR_NULL
+    for bad in (0, -16, 24):
+        assert L.turbo_stream_probe(fake, None, fake, bad, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_stream_probe(fake + 4, None, fake, 64, None) == tb.TURBO_ERR_ALIGN
+    assert L.turbo_stream_probe(fake, fake + 8, fake, 64, None) == tb.TURBO_ERR_ALIGN

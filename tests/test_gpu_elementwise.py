@@ -157,3 +157,24 @@ def test_elementwise_error_paths_need_no_gpu_work():
     assert L.turbo_add_bias_gelu(fake + 2, None, 4, 4, 0, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert L.turbo_add_bias_split_heads(fake, None, 1, 1, 0, 1, 1, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert L.turbo_merge_heads(fake, 1, 1, 1, 1, None, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+
+
+def test_stream_probe_copies_and_adds():
+    """The measurement aid behind the bench's stream ceilings: out = in0 (+ in1), exact in binary32."""
+    rng = np.random.Generator(np.random.Philox(16))
+    for n in (4, 1024 * 4, 1024 * 4 + 4, 3 * 4096 * 4 + 8, 1 << 20):
+        a, b = _rand(rng, (n,), F32), _rand(rng, (n,), F32)
+        out = torch.full((n + 8,), float("nan"), device="cuda")
+        tb.turbo_stream_probe(gu.dev(a), gu.dev(b), out[4:4 + n])
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(_np(out[4:4 + n]), a + b)
+        assert torch.isnan(out[:4]).all() and torch.isnan(out[4 + n:]).all()
+        ad = gu.dev(a)
+        tb.turbo_stream_probe(ad, None, ad)  # in place: the softmax mix
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(_np(ad), a)
+    h = _rand(rng, (4096,), F16)  # any dtype: the bytes are what is moved
+    od = torch.zeros(4096, dtype=torch.float16, device="cuda")
+    tb.turbo_stream_probe(gu.dev(h), None, od)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_np(od), h)
