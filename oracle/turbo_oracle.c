@@ -10,12 +10,12 @@
  * faster, so the oracle is the plain definition, one row at a time, in
  * double precision:
  *
- *   - Softmax "calculates summation and maximum" on the low dimension of a
+ *   - Softmax needs a row sum and a row maximum over the low dimension of a
  *     2-D view (Section 4.1.2); in attention it is applied to the scaled
  *     query-key dot products (Section 2.1).  The additive mask is the
  *     padding convention of Section 2.1 (short sequences are zero-padded to
  *     the longest one in the batch).
- *   - LayerNorm "calculates the mean and variance" (Section 4.1.2); the
+ *   - LayerNorm needs the row mean and the row variance (Section 4.1.2); the
  *     variance is the population variance of Equation 1.  The fused kernel
  *     ("AddBiasLayerNorm", Section 6.2.1) normalises x + bias + residual.
  *

@@ -1,6 +1,6 @@
-// Element-wise fused kernels that sit between two GEMMs (Section 4.1.1 of the paper: "fused activation functions
-// and fused transpose operations ... composed of element-wise operations"): bias + GELU, bias + head split, head
-// merge.  The paper prints no formula or layout for them; the readings are the ones the C header states.
+// Element-wise fused kernels that sit between two GEMMs (Section 4.1.1 of the paper names the fused activation and
+// the fused transposes as the non-GEMM kernels that consist of element-wise work only): bias + GELU, bias + head
+// split, head merge.  The paper prints no formula or layout for them; the readings are the ones the C header states.
 //
 // All three are pure streams (every element read once, written once), so the design is the one that reached the
 // copy ceiling in the reduction kernels: 16-byte non-temporal accesses, one short-lived workgroup per tile of
