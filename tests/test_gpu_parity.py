@@ -283,6 +283,33 @@ def test_layernorm_zero_rows_give_beta_and_single_column():
     np.testing.assert_allclose(got, np.broadcast_to(one.beta, got.shape), rtol=0, atol=1e-6)
 
 
+@pytest.mark.parametrize("path", [-1, 1, 2], ids=["planned", "block", "stream"])
+def test_layernorm_mean_far_from_zero_keeps_its_digits(path):
+    """Rows with |mean| = 1000 standard deviations: the case that separates the one-pass algorithms of Equation 1.
+
+    The inputs are exact for both sides (x alone, no bias or residual, so nothing is rounded before the statistics).
+    binary32 cannot hold the 1e-5 bar here: the mean itself is only known to ulp(1000) = 6.1e-5, which moves every
+    normalised output by up to that much in units of the standard deviation.  The bound used is 8 ulp(1000) ~ 5e-4
+    absolute on outputs of order one.  E(x^2) - E(x)^2 in binary32 would miss it by two orders of magnitude: it
+    subtracts two numbers near 1e6 whose ulp is 0.06 to get a variance of 1.
+    """
+    for hidden in (768, 1024, 4100):
+        case = wl.random_layernorm_case(73 + hidden, 64, hidden, eps=1e-5)
+        case.x[:] = (case.x + np.float32(1000.0)).astype(F32)
+        case.gamma[:] = 1
+        case.beta[:] = 0
+        with gu.overrides(path=path):
+            got = _np(gu.run_layernorm(case, residual=False, bias=False)).astype(np.float64)
+        want = gu.oracle_layernorm(case, residual=False, bias=False)
+        err = np.abs(got - want).max()
+        assert err < 8 * 6.1e-5, f"hidden={hidden}: max abs error {err:.2e}"
+        # the naive one-pass form, evaluated in binary32 on the same rows, is far outside that bound
+        x32 = case.x
+        naive_var = (x32 * x32).mean(-1, dtype=F32) - x32.mean(-1, dtype=F32) ** 2
+        naive = (x32 - x32.mean(-1, dtype=F32)[:, None]) / np.sqrt(np.maximum(naive_var, 0) + F32(1e-5))[:, None]
+        assert np.abs(naive - want).max() > 20 * err
+
+
 def test_softmax_degenerate_rows():
     # single key: weight 1 whatever the score
     case = wl.random_softmax_case(80, 2, 3, 4, 1)
