@@ -273,6 +273,44 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
     return rows
 
 
+def scheduler_table(torch, tb, wl, stream, launch, iters):
+    """The DP batch scheduler (Algorithm 2) fed with this build's own kernel times.
+
+    The step (softmax [b,12,L,L] with a key mask + add-bias-LayerNorm [b*L,768], fp32, cold) is timed on a grid of
+    lengths and batch sizes; turbo_cost_table_fill interpolates the per-request cost table; turbo_batch_schedule
+    splits config 2's 32 requests; each batch of the schedule is then timed at its own padded shape.  The cost is
+    that of the two kernels only (no GEMMs), so the schedule says what padding costs these kernels, nothing more."""
+    from paper_2010_05680_amd import serving as sv
+    base = wl.config_spec(2)
+    lengths = [int(v) for v in base.lengths]
+
+    def step_ms(b, L):
+        spec = wl.ConfigSpec(2, f"b{b}-len{L}", np.float32, b, base.H, L, L, base.score_std, base.scale, "key",
+                             b * L, base.hidden, base.eps, lengths=np.full(b, L, dtype=np.int64))
+        k = KernelSets(spec, torch, tb, wl, max_sets=8)
+        ms, _, _ = time_launches(torch, stream, lambda i: k.step(i, stream), iters, max(k.n_sm_sets, k.n_ln_sets), launch)
+        del k
+        return ms
+
+    sample_len, sample_batch = [16, 64, 128, 256, 384, 500], [1, 2, 4, 8, 16, 32]
+    per_request = np.array([[step_ms(b, L) / b for b in sample_batch] for L in sample_len])
+    torch.cuda.empty_cache()
+    table = sv.turbo_cost_table_fill(sample_len, sample_batch, per_request, 500, 32)
+    batches, predicted = sv.turbo_batch_schedule(lengths, table, 32)
+    shapes = [(len(b), max(lengths[i] for i in b)) for b in batches]
+    measured = sum(step_ms(b, L) for b, L in shapes)
+    padded = step_ms(len(lengths), max(lengths))
+    torch.cuda.empty_cache()
+    return {
+        "sampled_lengths": sample_len, "sampled_batch_sizes": sample_batch,
+        "per_request_us": [[round(v * 1e3, 3) for v in row] for row in per_request],
+        "schedule": [{"requests": b, "padded_to": L} for b, L in shapes],
+        "predicted_us": round(predicted * 1e3, 2), "measured_us": round(measured * 1e3, 2),
+        "one_padded_batch_us": round(padded * 1e3, 2),
+        "one_request_at_a_time_predicted_us": round(sum(table[n, 1] for n in lengths) * 1e3, 2),
+    }
+
+
 def cpu_baseline(spec, wl, budget_s=10.0):
     """The oracle as it stands, on the headline workload, on the host cores of this machine."""
     from oracle import turbo_oracle as orc
@@ -468,6 +506,7 @@ def main():
         result["per_config"] = per_config
         result["elementwise"] = elementwise_table(torch, tb, stream, args.launch, max(20, args.kernel_iters // 2))
         result["length_aware_config2"] = varlen_table(torch, tb, wl, stream, args.launch, max(20, args.kernel_iters // 2))
+        result["scheduler_on_measured_costs"] = scheduler_table(torch, tb, wl, stream, args.launch, max(20, args.kernel_iters // 2))
     print(json.dumps(result))
 
 

@@ -33,6 +33,24 @@ int turbo_batch_schedule(const int *lengths, int n, const double *cached_cost, i
                          int *batch_end, int *n_batches, double *total_cost);
 
 /*
+ * Cost table from samples (Section 6.3 describes two ways to obtain cached_cost: measure every (length, batch)
+ * pair in a warm-up phase, or, when there are too many, measure a sample of them and interpolate; entries may
+ * later be overwritten with measured values).  This call is the second way; the paper does not name the
+ * interpolation, the reading here is: the samples lie on a grid sample_len x sample_batch (both strictly
+ * increasing, values >= 1), the table entry for (len, b) is the bilinear interpolation of the four surrounding
+ * samples, and outside the grid the outermost cell's bilinear form is continued (a grid of one line is constant
+ * along that axis); results below zero are raised to zero.  At a sample point the entry equals the sample.
+ *
+ *   sample_cost  [n_len * n_batch], entry [i*n_batch + j] = cost PER REQUEST at (sample_len[i], sample_batch[j]).
+ *   cached_cost  out, dense [(max_len+1) * (max_batch+1)] as turbo_batch_schedule reads it; row 0 and column 0
+ *                are set to 0.  Overwriting single entries afterwards with measured costs is the caller's business
+ *                (the table is the caller's memory).
+ * Errors: TURBO_ERR_NULL, TURBO_ERR_SHAPE (empty or non-increasing grids, values < 1, max_len or max_batch <= 0).
+ */
+int turbo_cost_table_fill(const int *sample_len, int n_len, const int *sample_batch, int n_batch,
+                          const double *sample_cost, int max_len, int max_batch, double *cached_cost);
+
+/*
  * Sequence-length-aware allocator (Section 4.2, Algorithm 1): given the life time (first and last operator index
  * in topological order) and the size of every intermediate tensor of one inference, place each tensor at an offset
  * inside a chunk so that tensors whose life times overlap never share bytes, reusing the chunks kept from earlier

@@ -7,11 +7,13 @@
 * memory planning (Section 4.2, Algorithm 1): not a definition but a greedy heuristic, so the oracle takes the
   algorithm's steps in the paper's order and notation (FindGapFromChunk, MemAllocate), in plain Python, plus a
   checker of the property the plan must have: tensors whose life times overlap never share bytes.
+* cost table from samples (Section 6.3): bilinear weights over a sample grid, continued outside it.
 
 Pinned by tests/test_serving_host.py (hand cases, closed forms, invariants).  Shares nothing with the C++ code.
 """
 from __future__ import annotations
 
+import bisect
 import itertools
 import math
 from typing import Callable, List, Sequence, Tuple
@@ -44,6 +46,35 @@ def batch_schedule_exhaustive(lengths: Sequence[int], cost: Callable[[int, int],
             if c < best[0]:
                 best = (c, sizes)
     return best
+
+
+def _axis_weights(grid: Sequence[int], v: int):
+    """Two grid indices and their weights for linear inter-/extrapolation of position v on an increasing grid."""
+    if len(grid) == 1:
+        return 0, 0, 1.0, 0.0
+    hi = bisect.bisect_right(list(grid), v)          # first line beyond v
+    hi = min(max(hi, 1), len(grid) - 1)              # outside the grid: the outermost pair of lines
+    lo = hi - 1
+    t = (v - grid[lo]) / (grid[hi] - grid[lo])
+    return lo, hi, 1.0 - t, t
+
+
+def cost_table_from_samples(sample_len: Sequence[int], sample_batch: Sequence[int], sample_cost, max_len: int,
+                            max_batch: int):
+    """Dense per-request cost table [max_len+1][max_batch+1] from samples on a grid (Section 6.3, second strategy).
+
+    Reading (the paper only says "interpolation"): weighted sum of the four surrounding samples with the product of the
+    two axes' linear weights; outside the grid the weights of the outermost pair of lines are continued; negative
+    results become 0; row 0 and column 0 are 0."""
+    table = [[0.0] * (max_batch + 1) for _ in range(max_len + 1)]
+    for length in range(1, max_len + 1):
+        i0, i1, a0, a1 = _axis_weights(sample_len, length)
+        for b in range(1, max_batch + 1):
+            j0, j1, b0, b1 = _axis_weights(sample_batch, b)
+            v = (a0 * b0 * sample_cost[i0][j0] + a0 * b1 * sample_cost[i0][j1] +
+                 a1 * b0 * sample_cost[i1][j0] + a1 * b1 * sample_cost[i1][j1])
+            table[length][b] = max(v, 0.0)
+    return table
 
 
 # ---------------------------------------------------------------- memory planning (Algorithm 1)

@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_add_bias_layernorm",
     "turbo_add_bias_layernorm_dt", "turbo_add_bias_layernorm_varlen",
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
-    "turbo_batch_schedule", "turbo_mem_plan",
+    "turbo_batch_schedule", "turbo_mem_plan", "turbo_cost_table_fill",
     "turbo_status_string", "turbo_set_override", "turbo_describe_plan", "turbo_debug_fastdiv",
     "turbo_stream_probe",
 )

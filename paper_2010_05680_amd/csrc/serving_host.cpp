@@ -49,6 +49,58 @@ extern "C" int turbo_batch_schedule(const int* lengths, int n, const double* cac
 
 namespace {
 
+// Position of v on a strictly increasing grid g[0..n): the cell index i (0 <= i <= n-2) whose two lines bracket v,
+// or the outermost cell when v lies outside the grid, and the weight w of line i+1 (outside the grid w < 0 or > 1:
+// the cell's line is continued).  A grid of one line gives cell 0 with weight 0.
+void grid_cell(const int* g, int n, int v, int* cell, double* w) {
+    if (n == 1) {
+        *cell = 0;
+        *w = 0.0;
+        return;
+    }
+    int i = 0;
+    while (i < n - 2 && v >= g[i + 1]) ++i;
+    *cell = i;
+    *w = (double)(v - g[i]) / (double)(g[i + 1] - g[i]);
+}
+
+}  // namespace
+
+extern "C" int turbo_cost_table_fill(const int* sample_len, int n_len, const int* sample_batch, int n_batch,
+                                     const double* sample_cost, int max_len, int max_batch, double* cached_cost) {
+    if (!sample_len || !sample_batch || !sample_cost || !cached_cost) return TURBO_ERR_NULL;
+    if (n_len <= 0 || n_batch <= 0 || max_len <= 0 || max_batch <= 0) return TURBO_ERR_SHAPE;
+    for (int i = 0; i < n_len; ++i)
+        if (sample_len[i] < 1 || (i > 0 && sample_len[i] <= sample_len[i - 1])) return TURBO_ERR_SHAPE;
+    for (int j = 0; j < n_batch; ++j)
+        if (sample_batch[j] < 1 || (j > 0 && sample_batch[j] <= sample_batch[j - 1])) return TURBO_ERR_SHAPE;
+    const long long stride = (long long)max_batch + 1;
+    for (int len = 0; len <= max_len; ++len) {
+        int ci;
+        double wi;
+        grid_cell(sample_len, n_len, len, &ci, &wi);
+        const int ci1 = n_len > 1 ? ci + 1 : ci;
+        for (int b = 0; b <= max_batch; ++b) {
+            if (len == 0 || b == 0) {
+                cached_cost[len * stride + b] = 0.0;
+                continue;
+            }
+            int cj;
+            double wj;
+            grid_cell(sample_batch, n_batch, b, &cj, &wj);
+            const int cj1 = n_batch > 1 ? cj + 1 : cj;
+            const double c00 = sample_cost[(long long)ci * n_batch + cj], c01 = sample_cost[(long long)ci * n_batch + cj1];
+            const double c10 = sample_cost[(long long)ci1 * n_batch + cj], c11 = sample_cost[(long long)ci1 * n_batch + cj1];
+            const double lo = c00 + (c01 - c00) * wj, hi = c10 + (c11 - c10) * wj;
+            const double v = lo + (hi - lo) * wi;
+            cached_cost[len * stride + b] = v > 0.0 ? v : 0.0;  // a continued line may cross zero: costs do not
+        }
+    }
+    return TURBO_OK;
+}
+
+namespace {
+
 struct Placed {
     int tensor;
     long long offset;

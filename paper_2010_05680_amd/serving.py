@@ -21,6 +21,8 @@ def _lib():
         L.turbo_mem_plan.argtypes = [ip, ip, lp, ctypes.c_int, lp, ip, ctypes.c_int, ctypes.c_longlong, ctypes.c_double,
                                      ip, lp]
         L.turbo_mem_plan.restype = ctypes.c_int
+        L.turbo_cost_table_fill.argtypes = [ip, ctypes.c_int, ip, ctypes.c_int, dp, ctypes.c_int, ctypes.c_int, dp]
+        L.turbo_cost_table_fill.restype = ctypes.c_int
         _ready = True
     return L
 
@@ -51,6 +53,21 @@ def turbo_batch_schedule(lengths: Sequence[int], cached_cost: np.ndarray, max_ba
         batches.append([int(v) for v in order[begin:ends[k]]])
         begin = int(ends[k])
     return batches, total.value
+
+
+def turbo_cost_table_fill(sample_len: Sequence[int], sample_batch: Sequence[int], sample_cost: np.ndarray, max_len: int,
+                          max_batch: int) -> np.ndarray:
+    """sample_cost [len(sample_len), len(sample_batch)] per-request costs -> dense table [max_len+1, max_batch+1]."""
+    sl, sb = _ints(sample_len), _ints(sample_batch)
+    sc = np.ascontiguousarray(sample_cost, dtype=np.float64)
+    if sc.shape != (len(sl), len(sb)):
+        raise ValueError("sample_cost must be [len(sample_len), len(sample_batch)]")
+    table = np.zeros((max(max_len, 0) + 1, max(max_batch, 0) + 1), np.float64)
+    ip, dp = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)
+    st = _lib().turbo_cost_table_fill(sl.ctypes.data_as(ip), len(sl), sb.ctypes.data_as(ip), len(sb), sc.ctypes.data_as(dp),
+                                      int(max_len), int(max_batch), table.ctypes.data_as(dp))
+    _b._check(st, "turbo_cost_table_fill")
+    return table
 
 
 def turbo_mem_plan(first_op, last_op, size, chunk_sizes: Sequence[int], default_chunk_size: int = 2 << 20,

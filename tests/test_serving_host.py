@@ -103,6 +103,75 @@ def test_scheduler_rejects_bad_input():
     assert L.turbo_batch_schedule(None, 1, None, 1, 1, None, None, None, None) == tb.TURBO_ERR_NULL
 
 
+# ------------------------------------------------------------------ cost table from samples
+
+SAMPLE_LEN, SAMPLE_BATCH = [8, 64, 200, 500], [1, 4, 16]
+
+
+def test_cost_table_oracle_reproduces_samples_and_bilinear_models_exactly():
+    """Pins: equality at the sample points; a cost of the form a + b*len + c*batch + d*len*batch is reproduced
+    everywhere, inside and outside the grid (closed form); one sampled length or batch size means constant along
+    that axis; continued lines that would go negative stop at zero."""
+    model = lambda L, b: 3.0 + 0.25 * L + 1.5 * b + 0.01 * L * b
+    samples = [[model(L, b) for b in SAMPLE_BATCH] for L in SAMPLE_LEN]
+    table = so.cost_table_from_samples(SAMPLE_LEN, SAMPLE_BATCH, samples, 600, 20)
+    for L in range(1, 601):
+        for b in range(1, 21):
+            assert table[L][b] == pytest.approx(model(L, b), rel=1e-12)
+    bumpy = [[math.sin(L) + 0.1 * b * b + 5 for b in SAMPLE_BATCH] for L in SAMPLE_LEN]
+    table = so.cost_table_from_samples(SAMPLE_LEN, SAMPLE_BATCH, bumpy, 500, 16)
+    for i, L in enumerate(SAMPLE_LEN):
+        for j, b in enumerate(SAMPLE_BATCH):
+            assert table[L][b] == pytest.approx(bumpy[i][j], rel=1e-12)
+    assert all(table[0][b] == 0 for b in range(17)) and all(table[L][0] == 0 for L in range(501))
+    flat = so.cost_table_from_samples([100], [2], [[7.0]], 300, 8)
+    assert all(flat[L][b] == 7.0 for L in range(1, 301) for b in range(1, 9))
+    falling = so.cost_table_from_samples([10, 20], [1], [[10.0], [1.0]], 40, 1)
+    assert falling[30][1] == 0.0 and falling[15][1] == pytest.approx(5.5)
+
+
+def test_cost_table_oracle_matches_library_interpolation_inside_the_grid():
+    from scipy.interpolate import RegularGridInterpolator
+    rng = np.random.default_rng(5)
+    samples = rng.uniform(1, 9, size=(len(SAMPLE_LEN), len(SAMPLE_BATCH)))
+    table = np.array(so.cost_table_from_samples(SAMPLE_LEN, SAMPLE_BATCH, samples.tolist(), 500, 16))
+    f = RegularGridInterpolator((SAMPLE_LEN, SAMPLE_BATCH), samples, method="linear")
+    pts = np.array([(L, b) for L in range(8, 501) for b in range(1, 17)], dtype=float)
+    np.testing.assert_allclose(table[8:501, 1:17].reshape(-1), f(pts), rtol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_cost_table_matches_oracle(seed):
+    rng = np.random.default_rng(100 + seed)
+    n_len, n_batch = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+    sl = np.sort(rng.choice(np.arange(1, 300), size=n_len, replace=False)).tolist()
+    sb = np.sort(rng.choice(np.arange(1, 33), size=n_batch, replace=False)).tolist()
+    sc = rng.uniform(0.5, 20, size=(n_len, n_batch))
+    got = sv.turbo_cost_table_fill(sl, sb, sc, 320, 40)
+    want = np.array(so.cost_table_from_samples(sl, sb, sc.tolist(), 320, 40))
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    for i, L in enumerate(sl):
+        for j, b in enumerate(sb):
+            assert got[L, b] == pytest.approx(sc[i, j], rel=1e-13)
+
+
+def test_cost_table_feeds_the_scheduler_and_rejects_bad_grids():
+    # samples of the affine model behind the paper's example, taken at a few lengths and batch sizes only
+    model = lambda L, b: (20.0 + L * b) / b
+    sl, sb = [10, 40, 80], [1, 2, 5]
+    table = sv.turbo_cost_table_fill(sl, sb, np.array([[model(L, b) for b in sb] for L in sl]), 80, 5)
+    lengths = [77, 17, 63, 18, 52]
+    batches, _ = sv.turbo_batch_schedule(lengths, table, 5)
+    assert [[lengths[i] for i in b] for b in batches] == [[17, 18], [52, 63], [77]]
+    with pytest.raises(tb.TurboError):
+        sv.turbo_cost_table_fill([10, 10], [1], np.ones((2, 1)), 20, 2)   # grid not strictly increasing
+    with pytest.raises(tb.TurboError):
+        sv.turbo_cost_table_fill([0, 10], [1], np.ones((2, 1)), 20, 2)    # length 0
+    with pytest.raises(tb.TurboError):
+        sv.turbo_cost_table_fill([5], [1], np.ones((1, 1)), 0, 2)
+    assert sv._lib().turbo_cost_table_fill(None, 1, None, 1, None, 1, 1, None) == tb.TURBO_ERR_NULL
+
+
 # ------------------------------------------------------------------ allocator: oracle pins
 
 def test_allocator_oracle_reuses_space_of_dead_tensors():
