@@ -275,6 +275,38 @@ def test_allocator_across_consecutive_requests(seqs):
         assert len(held_cpp) >= len(chunks200)  # the longer request keeps the chunks and may add to them
 
 
+@pytest.mark.parametrize("seq", [17, 128, 493])
+def test_one_layer_plan_is_reused_by_every_repeated_layer(seq):
+    """Section 6.2.2's way to keep the O(#tensor^2) planner cheap: plan the tensors of ONE of the repeated layers
+    and use the same offsets in all of them.  What makes that valid is the record given to the tensor that crosses
+    the layer boundary (a layer's output is the next layer's input and residual): it lives for the whole layer in
+    the one-layer plan.  Checked by unrolling 12 layers with the one-layer offsets and running the plan checker
+    over all 12 * 12 + 1 tensors with their true life times."""
+    ops = 12  # operators per layer
+    first, last, size = _bert_like_records(seq)
+    carried = 4 * seq * 768
+    f1, l1, s1 = first + [0], last + [ops - 1], size + [carried]
+    chunk, offset, chunks = sv.turbo_mem_plan(f1, l1, s1, [])
+    assert so.plan_violations(f1, l1, s1, chunk, offset, chunks) == []
+    layers = 12
+    uf, ul, us, uc, uo = [], [], [], [], []
+    for k in range(layers):
+        for t in range(len(first)):
+            uf.append(first[t] + k * ops)
+            ul.append(last[t] + k * ops)
+            us.append(size[t]); uc.append(chunk[t]); uo.append(offset[t])
+    # boundary tensors: the model input feeds layer 0; layer k's output (written by its last operator) is read by
+    # layer k+1 up to its residual add (operator 7)
+    uf.append(0); ul.append(7); us.append(carried); uc.append(chunk[-1]); uo.append(offset[-1])
+    for k in range(layers):
+        uf.append(k * ops + ops - 1)
+        ul.append(min((k + 1) * ops + 7, layers * ops - 1))
+        us.append(carried); uc.append(chunk[-1]); uo.append(offset[-1])
+    assert so.plan_violations(uf, ul, us, uc, uo, chunks) == []
+    # and the footprint is that of one layer, not of twelve
+    assert sum(chunks) <= max(2 << 20, 1.2 * so.peak_live_bytes(f1, l1, s1)) + len(chunks) * (2 << 20)
+
+
 def test_allocator_rejects_bad_input():
     with pytest.raises(tb.TurboError):
         sv.turbo_mem_plan([2], [1], [10], [])          # last before first
