@@ -91,7 +91,7 @@ int turbo_masked_softmax_ex(void *scores, const void *mask, long long mask_strid
  * For real rows this equals turbo_masked_softmax_ex with a 0 / -10000 key mask (where exp() underflows to the
  * same exact zeros).  k_lengths, q_lengths: DEVICE int32 arrays [B]; q_lengths may be NULL (all Sq rows are
  * computed); for self-attention pass the same array twice.  Lengths are clamped to 0..Sk; a request with
- * k_lengths[b] = 0 is left untouched.  Rows of more than 32768 elements are not supported (TURBO_ERR_SHAPE).
+ * k_lengths[b] = 0 is left untouched.
  */
 int turbo_masked_softmax_varlen(void *scores, const int *q_lengths, const int *k_lengths, int B, int H, int Sq, int Sk,
                                 float scale, int dtype, void *stream);

@@ -89,7 +89,6 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
         ovr.no_full = 1;
     }
     const turbo::Plan plan = turbo::make_plan(Sk, es, align_elems, n_rows, turbo::kSoftmaxLimits, ovr);
-    if (k_lengths != nullptr && plan.path == turbo::kPathStream) return TURBO_ERR_SHAPE;
 
     turbo::SoftmaxArgs a;
     a.scores = scores;

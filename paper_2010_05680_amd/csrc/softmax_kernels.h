@@ -346,9 +346,13 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 
 // stream family: rows too long for registers.  First sweep keeps a running
 // (max, sum) per lane, rescaling the sum whenever the maximum grows; after the
-// combine a second sweep re-reads the row and writes the result.
-template <typename T, int VEC, bool MASK>
+// combine a second sweep re-reads the row and writes the result.  With
+// per-request lengths the first sweep stops at the row's last valid key and the
+// second writes zeros beyond it without reading; rows without valid keys are skipped.
+template <typename T, int VEC, int MK>
 __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxArgs a) {
+    constexpr bool MASK = MK == kMaskAdditive;
+    constexpr bool VARLEN = MK == kMaskLengths;
     __shared__ SoftmaxLds lds;
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int tid = threadIdx.x;
@@ -360,12 +364,17 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
     const int step = (int)blockDim.x * VEC;
 
     int slot = 0;
-    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x, slot ^= 1) {
+    for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
+        int klen = Sk;
+        if constexpr (VARLEN) {
+            klen = row_key_count(a, row);
+            if (klen == 0) continue;  // the whole workgroup skips the row together
+        }
         T* rp = scores + (long long)row * Sk;
         const T* mp = mask_row_ptr<T, MASK>(a, row);
 
         float m_run = -INFINITY, l_run = 0.f;
-        for (long long col = (long long)tid * VEC; col < Sk; col += step) {
+        for (long long col = (long long)tid * VEC; col < klen; col += step) {
             Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);  // plain: the row is read again below
             Pack<T, VEC> mraw;
             if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
@@ -378,6 +387,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
                     z[j] = fmaf(s, scale, (float)mraw.v[j]);
                 else
                     z[j] = s * scale;
+                if constexpr (VARLEN) z[j] = col + j < klen ? z[j] : -INFINITY;  // element 0 of the vector is valid
                 cm = fmaxf(cm, z[j]);
             }
             if (cm > m_run) {
@@ -398,25 +408,32 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
 
         // factor = exp(m_w - M) / L; the second sweep needs exp(z - M)/L, so fold m_w back in
         const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
-        // exp2((z - m_w) log2e) * f == exp(z - M)/L; a wavefront with no element stores nothing
+        // exp2((z - m_w) log2e) * f == exp(z - M)/L; a wavefront with no element stores nothing but zeros
         const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
         for (long long col = (long long)tid * VEC; col < Sk; col += step) {
-            Pack<T, VEC> raw = load_stream<T, VEC>(rp + col);
-            Pack<T, VEC> mraw;
-            if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
             Pack<T, VEC> o;
+            if (VARLEN && col >= klen) {
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                float s = (float)raw.v[j];
-                float zz;
-                if constexpr (MASK)
-                    zz = fmaf(s, scale, (float)mraw.v[j]);
-                else
-                    zz = s * scale;
-                o.v[j] = (T)(fast_exp2(fmaf(zz, kLog2e, shift)) * f);
+                for (int j = 0; j < VEC; ++j) o.v[j] = (T)0.f;
+            } else {
+                Pack<T, VEC> raw = load_stream<T, VEC>(rp + col);
+                Pack<T, VEC> mraw;
+                if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float s = (float)raw.v[j];
+                    float zz;
+                    if constexpr (MASK)
+                        zz = fmaf(s, scale, (float)mraw.v[j]);
+                    else
+                        zz = s * scale;
+                    const float y = fast_exp2(fmaf(zz, kLog2e, shift)) * f;
+                    o.v[j] = (T)((!VARLEN || col + j < klen) ? y : 0.f);
+                }
             }
             store_stream<T, VEC>(rp + col, o);
         }
+        slot ^= 1;  // only rows that used the LDS slot advance it (skipped rows execute no barrier)
     }
 }
 
@@ -498,13 +515,9 @@ hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCf
         }
         return hipErrorInvalidValue;
     }
-    if constexpr (MK == kMaskLengths) {
-        return hipErrorInvalidValue;  // the two-sweep kernels do not take per-request lengths
-    } else {
-        hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MK == kMaskAdditive>),
-                           dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
-        return hipGetLastError();
-    }
+    hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MK>),
+                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
+    return hipGetLastError();
 }
 
 // UA_OK: the under-aligned flavour exists only for the widest vector of each element type.

@@ -29,7 +29,7 @@ def _run_softmax(scores, q_len, k_len, scale):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16])
-@pytest.mark.parametrize("path", [-1, tb.PATH_WAVE, tb.PATH_BLOCK])
+@pytest.mark.parametrize("path", [-1, tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
 def test_varlen_softmax_shapes(dtype, path):
     rng = np.random.Generator(np.random.Philox(21))
     for B, H, S in [(1, 1, 1), (3, 2, 7), (4, 3, 16), (5, 2, 33), (6, 2, 64), (4, 2, 100), (3, 2, 128), (4, 1, 257), (2, 1, 493),
@@ -48,6 +48,28 @@ def test_varlen_softmax_shapes(dtype, path):
             if q_len is not None:
                 for b in range(B):
                     np.testing.assert_array_equal(got[b, :, lens[b]:, :], scores[b, :, lens[b]:, :])
+
+
+def test_varlen_softmax_rows_too_long_for_registers():
+    """Rows beyond 32768 keys go through the two-sweep kernels; padding is poisoned with NaN."""
+    rng = np.random.Generator(np.random.Philox(24))
+    for dtype, S_k in ((F32, 40000), (F16, 70008), (F32, 33001)):
+        B, H, S_q = 3, 2, 3
+        scores = (rng.standard_normal((B, H, S_q, S_k), dtype=np.float32) * 3).astype(dtype)
+        k_len = np.array([S_k, 1, S_k // 2 + 3])
+        q_len = np.array([3, 2, 0])
+        poisoned = scores.copy()
+        for b in range(B):
+            poisoned[b, :, :, k_len[b]:] = np.nan
+            poisoned[b, :, q_len[b]:, :] = np.nan
+        got = _np(_run_softmax(poisoned, q_len, k_len, 0.125))
+        want = orc.masked_softmax_varlen(scores, q_len, k_len, 0.125)
+        for b in range(B):
+            live = got[b, :, :q_len[b], :]
+            if q_len[b] > 0:
+                assert_parity(live, want[b, :, :q_len[b], :], dtype, f"varlen two-sweep softmax Sk={S_k} request {b}")
+                assert (live[..., k_len[b]:] == 0).all()
+            assert np.isnan(got[b, :, q_len[b]:, :]).all(), "a padding row was written"
 
 
 def test_varlen_softmax_ignores_what_lies_beyond_the_lengths():
@@ -123,7 +145,7 @@ def test_varlen_error_paths():
     fake = 0x10000
     assert L.turbo_masked_softmax_varlen(fake, None, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
     assert L.turbo_masked_softmax_varlen(fake, None, fake + 2, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
-    assert L.turbo_masked_softmax_varlen(fake, None, fake, 1, 1, 4, 70000, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_masked_softmax_varlen(fake, None, fake, 1, 1, 0, 70000, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert L.turbo_add_bias_layernorm_varlen(fake, fake, fake, fake, fake, None, 1, 4, 8, 1e-5, fake, tb.TURBO_F32, None) \
         == tb.TURBO_ERR_NULL
     assert L.turbo_add_bias_layernorm_varlen(fake, fake, fake, fake, fake, fake, 0, 4, 8, 1e-5, fake, tb.TURBO_F32, None) \
