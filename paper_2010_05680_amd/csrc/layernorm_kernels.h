@@ -23,6 +23,17 @@ namespace turbo {
 #define TURBO_LN_PRELOAD_ELEMS 16
 #endif
 constexpr int kParamPreloadElems = TURBO_LN_PRELOAD_ELEMS;     // keep bias/gamma/beta in registers up to this many columns per lane
+// The block family runs with 128 registers per lane (1024-thread workgroups) and also holds the next row's loads:
+// at 16 columns per lane the three parameter vectors no longer fit beside them unless the row mode is the one
+// without bounds checks.
+#ifndef TURBO_LN_BLOCK_PRELOAD_ELEMS
+#define TURBO_LN_BLOCK_PRELOAD_ELEMS 12
+#endif
+#ifndef TURBO_LN_BLOCK_PRELOAD_FULL_ELEMS
+#define TURBO_LN_BLOCK_PRELOAD_FULL_ELEMS 16
+#endif
+constexpr int kBlockParamPreloadElems = TURBO_LN_BLOCK_PRELOAD_ELEMS;
+constexpr int kBlockParamPreloadFullElems = TURBO_LN_BLOCK_PRELOAD_FULL_ELEMS;
 
 struct LayerNormArgs {
     const void* x;
@@ -320,7 +331,7 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     __shared__ LayerNormLds lds;
-    constexpr bool PRELOAD = NV * VEC <= kParamPreloadElems;
+    constexpr bool PRELOAD = NV * VEC <= (FULL ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
@@ -556,6 +567,13 @@ hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hi
     return hipGetLastError();
 }
 
+// The shapes the planner can ask for (same rule as make_plan's register budget for the block family).
+template <typename T, int VEC, int NV>
+constexpr bool block_shape_compiled() {
+    return (NV * VEC <= kLayerNormLimits.block_max_epl || NV == 1) &&
+           (VEC * (int)sizeof(T) >= 16 || NV <= kLayerNormLimits.block_max_nv_narrow);
+}
+
 template <typename T, int VEC, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>),
@@ -597,15 +615,15 @@ hipError_t launch_layernorm_vr(const Plan& p, const LayerNormArgs& a, const Laun
     }
     if (p.path == kPathBlock) {
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kLayerNormLimits.block_max_epl || 1 == 1) return launch_layernorm_block<T, VEC, 1, RES, MODE>(p, a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kLayerNormLimits.block_max_epl || 2 == 1) return launch_layernorm_block<T, VEC, 2, RES, MODE>(p, a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kLayerNormLimits.block_max_epl || 3 == 1) return launch_layernorm_block<T, VEC, 3, RES, MODE>(p, a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kLayerNormLimits.block_max_epl || 4 == 1) return launch_layernorm_block<T, VEC, 4, RES, MODE>(p, a, lc, s); else break;
-            case 5: if constexpr (5 * VEC <= kLayerNormLimits.block_max_epl) return launch_layernorm_block<T, VEC, 5, RES, MODE>(p, a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kLayerNormLimits.block_max_epl || 6 == 1) return launch_layernorm_block<T, VEC, 6, RES, MODE>(p, a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kLayerNormLimits.block_max_epl || 8 == 1) return launch_layernorm_block<T, VEC, 8, RES, MODE>(p, a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kLayerNormLimits.block_max_epl || 12 == 1) return launch_layernorm_block<T, VEC, 12, RES, MODE>(p, a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kLayerNormLimits.block_max_epl || 16 == 1) return launch_layernorm_block<T, VEC, 16, RES, MODE>(p, a, lc, s); else break;
+            case 1: if constexpr (block_shape_compiled<T, VEC, 1>()) return launch_layernorm_block<T, VEC, 1, RES, MODE>(p, a, lc, s); else break;
+            case 2: if constexpr (block_shape_compiled<T, VEC, 2>()) return launch_layernorm_block<T, VEC, 2, RES, MODE>(p, a, lc, s); else break;
+            case 3: if constexpr (block_shape_compiled<T, VEC, 3>()) return launch_layernorm_block<T, VEC, 3, RES, MODE>(p, a, lc, s); else break;
+            case 4: if constexpr (block_shape_compiled<T, VEC, 4>()) return launch_layernorm_block<T, VEC, 4, RES, MODE>(p, a, lc, s); else break;
+            case 5: if constexpr (block_shape_compiled<T, VEC, 5>()) return launch_layernorm_block<T, VEC, 5, RES, MODE>(p, a, lc, s); else break;
+            case 6: if constexpr (block_shape_compiled<T, VEC, 6>()) return launch_layernorm_block<T, VEC, 6, RES, MODE>(p, a, lc, s); else break;
+            case 8: if constexpr (block_shape_compiled<T, VEC, 8>()) return launch_layernorm_block<T, VEC, 8, RES, MODE>(p, a, lc, s); else break;
+            case 12: if constexpr (block_shape_compiled<T, VEC, 12>()) return launch_layernorm_block<T, VEC, 12, RES, MODE>(p, a, lc, s); else break;
+            case 16: if constexpr (block_shape_compiled<T, VEC, 16>()) return launch_layernorm_block<T, VEC, 16, RES, MODE>(p, a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }

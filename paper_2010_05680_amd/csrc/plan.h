@@ -38,6 +38,8 @@ struct OpLimits {
     int block_pref_nv;   // block: grow the workgroup until a lane holds at most this many vectors
     int block_max_epl;   // block: most elements per lane (1024 threads leave 128 VGPRs each)
     int block_from_bytes;  // rows of at least this many bytes go to the block family even if a wavefront could hold them
+    int block_max_nv_narrow;  // block: most vectors per lane when a vector is narrower than 16 bytes (every vector
+                              // costs address registers, whatever its width)
 };
 #ifndef TURBO_SM_TARGET_ELEMS
 #define TURBO_SM_TARGET_ELEMS 32
@@ -57,8 +59,8 @@ struct OpLimits {
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
 #define TURBO_LN_BLOCK_FROM_BYTES (1 << 30)
 #endif
-constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES};
-constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES};
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6};
 
 struct Plan {
     int path;    // PathKind
@@ -168,7 +170,8 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
             long long per_lane = (nvec + 64 * w - 1) / (64 * w);
             if (per_lane > kMaxNV) continue;
             int nv = round_up_nv((int)per_lane);
-            const bool fits = nv * vec <= lim.block_max_epl || nv == 1;
+            const bool fits = (nv * vec <= lim.block_max_epl || nv == 1) &&
+                              (vec * elem_size >= 16 || nv <= lim.block_max_nv_narrow);
             if (fits && nv <= max_nv) {
                 block_ok = true;
                 block_w = w;

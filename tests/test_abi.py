@@ -198,3 +198,18 @@ def test_stream_probe_rejects_bad_arguments_without_a_gpu():
         assert L.turbo_stream_probe(fake, None, fake, bad, None) == tb.TURBO_ERR_SHAPE
     assert L.turbo_stream_probe(fake + 4, None, fake, 64, None) == tb.TURBO_ERR_ALIGN
     assert L.turbo_stream_probe(fake, fake + 8, fake, 64, None) == tb.TURBO_ERR_ALIGN
+
+
+def test_no_kernel_of_the_built_library_spills_registers():
+    """The build writes one line per kernel from hipcc's resource-usage remarks and refuses to link when a kernel
+    needs scratch memory (spills would be memory traffic the byte counts do not show).  When that report is there,
+    check it again here; a library copied in without its build folder is skipped."""
+    import os
+    from paper_2010_05680_amd import build as tbuild
+    report = os.path.join(tbuild.OBJ_DIR, tbuild.RESOURCE_FILE)
+    if not os.path.exists(report):
+        pytest.skip("no build report beside the library")
+    lines = [ln.split() for ln in open(report) if ln.strip()]
+    assert len(lines) > 100
+    bad = [ln[0] for ln in lines if "scratch=0" not in ln or "vgpr_spill=0" not in ln]
+    assert bad == []

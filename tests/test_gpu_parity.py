@@ -125,7 +125,7 @@ def test_softmax_ragged_row_lengths(dtype, kind, wide):
 
 
 RAGGED_HIDDEN = [1, 2, 3, 5, 8, 9, 63, 64, 100, 255, 256, 257, 768, 771, 1000, 1024, 1027, 1536, 1540, 2048, 3001, 4096, 4100, 4101,
-                 6144, 6147]
+                 6144, 6147, 8000, 8190, 8192, 12288, 16000, 16382, 16384, 16388]
 
 
 @pytest.mark.parametrize("wide", [True, False], ids=["element-aligned-wide", "aligned-narrow"])
