@@ -570,7 +570,8 @@ hipError_t launch_layernorm_wave(const LayerNormArgs& a, const LaunchCfg& lc, hi
 // The shapes the planner can ask for (same rule as make_plan's register budget for the block family).
 template <typename T, int VEC, int NV>
 constexpr bool block_shape_compiled() {
-    return (NV * VEC <= kLayerNormLimits.block_max_epl || NV == 1) &&
+    return (NV * VEC <= ((sizeof(T) == 2 && VEC == 8) ? kLayerNormLimits.block_max_epl_2byte : kLayerNormLimits.block_max_epl) ||
+            NV == 1) &&
            (VEC * (int)sizeof(T) >= 16 || NV <= kLayerNormLimits.block_max_nv_narrow);
 }
 

@@ -40,6 +40,11 @@ struct OpLimits {
     int block_from_bytes;  // rows of at least this many bytes go to the block family even if a wavefront could hold them
     int block_max_nv_narrow;  // block: most vectors per lane when a vector is narrower than 16 bytes (every vector
                               // costs address registers, whatever its width)
+    int block_max_epl_2byte;  // block: most elements per lane for 16-byte vectors of 2-byte elements (their loads take
+                              // half the registers)
+    int block_wide_from_16ths;  // block: 16 wavefronts x 2 vectors replace fewer wavefronts x >= 3 vectors once they
+                                // would use at least this many 16ths of their lanes; 0 = never (measured per operation)
+    int block_wide_from_16ths_2byte;  // the same for 2-byte elements
 };
 #ifndef TURBO_SM_TARGET_ELEMS
 #define TURBO_SM_TARGET_ELEMS 32
@@ -59,8 +64,8 @@ struct OpLimits {
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
 #define TURBO_LN_BLOCK_FROM_BYTES (1 << 30)
 #endif
-constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16};
-constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6};
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0};
 
 struct Plan {
     int path;    // PathKind
@@ -163,6 +168,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     // 16 wavefronts with whatever still fits the register budget.
     bool block_ok = false;
     int block_w = 0, block_nv = 0;
+    const int block_max_epl = (elem_size == 2 && vec * elem_size >= 16) ? lim.block_max_epl_2byte : lim.block_max_epl;
     for (int pass = 0; pass < 3 && !block_ok; ++pass) {
         const int max_w = pass == 0 ? 8 : kBlockMaxWaves;
         const int max_nv = pass == 0 ? lim.block_pref_nv : pass == 1 ? 2 * lim.block_pref_nv : kMaxNV;
@@ -170,7 +176,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
             long long per_lane = (nvec + 64 * w - 1) / (64 * w);
             if (per_lane > kMaxNV) continue;
             int nv = round_up_nv((int)per_lane);
-            const bool fits = (nv * vec <= lim.block_max_epl || nv == 1) &&
+            const bool fits = (nv * vec <= block_max_epl || nv == 1) &&
                               (vec * elem_size >= 16 || nv <= lim.block_max_nv_narrow);
             if (fits && nv <= max_nv) {
                 block_ok = true;
@@ -179,6 +185,16 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
                 break;
             }
         }
+    }
+    // Measured for the softmax: a workgroup of 16 wavefronts with 2 vectors per lane streams better than 8 with
+    // 3 or 4, provided enough of its lanes have work (rows of 1536..2048 vectors of binary32, 1792..2048 of binary16;
+    // below that the idle lanes cost more than the shape gains).
+    const int wide_from = elem_size == 2 ? lim.block_wide_from_16ths_2byte : lim.block_wide_from_16ths;
+    if (block_ok && wide_from > 0 && block_w < kBlockMaxWaves && block_nv >= 3 &&
+        nvec <= 2LL * 64 * kBlockMaxWaves && 16 * nvec >= (long long)wide_from * 2 * 64 * kBlockMaxWaves &&
+        2 * vec <= block_max_epl && vec * elem_size >= 16) {
+        block_w = kBlockMaxWaves;
+        block_nv = 2;
     }
 
     int path;

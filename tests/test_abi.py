@@ -158,7 +158,8 @@ def test_planner_invariants_over_many_shapes():
     lens = list(range(1, 300)) + [int(v) for v in rng.integers(300, 70000, size=400)] + \
         [512, 768, 1024, 1280, 1536, 2048, 2560, 3072, 4096, 5120, 8192, 16384, 32768, 32772, 65536, 100000]
     supported_nv = {1, 2, 3, 4, 5, 6, 8, 12, 16}
-    for op, wave_max, block_max in ((0, 64, 32), (1, 24, 16)):
+    # (operation, most elements per lane: wave family, block family, block family with 16-byte vectors of 2-byte elements)
+    for op, wave_max, block_max, block_max_2byte in ((0, 64, 32, 32), (1, 24, 16, 24)):
         for dtype, es in ((tb.TURBO_F32, 4), (tb.TURBO_F16, 2)):
             for L in lens:
                 for aligned in (True, False):
@@ -182,7 +183,10 @@ def test_planner_invariants_over_many_shapes():
                         elif fam == "block":
                             w, nv = kv["waves"], kv["nv"]
                             assert w in (2, 4, 8, 16) and nv in supported_nv, what
-                            assert 64 * w * nv >= nvec and (nv * vec <= block_max or nv == 1), what
+                            budget = block_max_2byte if (es == 2 and vec == 8) else block_max
+                            assert 64 * w * nv >= nvec and (nv * vec <= budget or nv == 1), what
+                            if vec * es < 16 and op == 1:
+                                assert nv <= 6, what  # narrow vectors: every one of them costs address registers
                             if mode == "f":
                                 assert 64 * w * nv * vec == L, what
                         else:
