@@ -249,6 +249,31 @@ void oracle_masked_softmax_varlen(const double *scores, const int *q_len, const 
     }
 }
 
+/* Row-packed variable-length batch: no padding in memory.  Request b holds its scores as [H][len_b][len_b],
+ * the requests follow one another (request b starts at element H * sum_{i<b} len_i^2).  Every row of len_b keys is
+ * normalised: y = softmax(scale * s) over the row.  `scores` and `out` hold H * sum len_b^2 values. */
+void oracle_masked_softmax_packed(const double *scores, const int *len, int B, int H, double scale, double *out)
+{
+    long long base = 0;
+    for (int b = 0; b < B; ++b) {
+        const long long n = len[b];
+        for (int h = 0; h < H; ++h)
+            for (long long q = 0; q < n; ++q) {
+                const double *s = scores + base + (h * n + q) * n;
+                double *y = out + base + (h * n + q) * n;
+                double m = -INFINITY, l = 0.0;
+                for (long long k = 0; k < n; ++k)
+                    if (scale * s[k] > m) m = scale * s[k];
+                for (long long k = 0; k < n; ++k) {
+                    y[k] = exp(scale * s[k] - m);
+                    l += y[k];
+                }
+                for (long long k = 0; k < n; ++k) y[k] /= l;
+            }
+        base += (long long)H * n * n;
+    }
+}
+
 /* x, residual, out_before, out are [B][S][hidden].  Token rows s < len[b] get LayerNorm(x + bias + residual)
  * * gamma + beta; padding rows keep out_before. */
 void oracle_add_bias_layernorm_varlen(const double *x, const double *residual, const double *bias,

@@ -58,6 +58,8 @@ def _load():
         lib.oracle_masked_softmax_varlen.argtypes = [_dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                      ctypes.c_int, ctypes.c_double, _dp]
         lib.oracle_masked_softmax_varlen.restype = None
+        lib.oracle_masked_softmax_packed.argtypes = [_dp, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_double, _dp]
+        lib.oracle_masked_softmax_packed.restype = None
         lib.oracle_add_bias_layernorm_varlen.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int,
                                                          ctypes.c_int, ctypes.c_double, _dp, _dp]
         lib.oracle_add_bias_layernorm_varlen.restype = None
@@ -215,6 +217,19 @@ def masked_softmax_varlen(scores, q_lengths, k_lengths, scale: float = 1.0) -> n
     out = np.empty_like(s)
     if s.size:
         _load().oracle_masked_softmax_varlen(_ptr(s), _iptr(ql), _iptr(kl), B, H, Sq, Sk, float(scale), _ptr(out))
+    return out
+
+
+def masked_softmax_packed(scores, lengths, H: int, scale: float = 1.0) -> np.ndarray:
+    """Row-packed batch: `scores` is the flat concatenation of the requests' [H, len_b, len_b] blocks (no padding);
+    every row of len_b keys becomes softmax(scale * row).  Returns the flat result."""
+    s = _f64(scores).reshape(-1)
+    ln = _i32(lengths)
+    if ln.ndim != 1 or (ln < 0).any() or int(H) * int((ln.astype(np.int64) ** 2).sum()) != s.size:
+        raise ValueError("scores must hold H * sum(len^2) values")
+    out = np.empty_like(s)
+    if s.size:
+        _load().oracle_masked_softmax_packed(_ptr(s), _iptr(ln), len(ln), int(H), float(scale), _ptr(out))
     return out
 
 

@@ -46,6 +46,10 @@ MUTATIONS = [
     ("varlen_softmax_tail_not_zeroed", "for (int k = kl; k < Sk; ++k) y[k] = 0.0;", "for (int k = kl; k < Sk; ++k) y[k] = s[k];"),
     ("varlen_softmax_ignores_query_lengths", "int active = kl > 0 && (q_len == NULL || q < q_len[b]);", "int active = kl > 0;"),
     ("varlen_layernorm_off_by_one_row", "if (s < len[b])\n                oracle_add_bias_layernorm(", "if (s <= len[b])\n                oracle_add_bias_layernorm("),
+    ("packed_request_offset_forgets_the_heads", "base += (long long)H * n * n;", "base += n * n;"),
+    ("packed_row_stride_wrong", "const double *s = scores + base + (h * n + q) * n;", "const double *s = scores + base + (h * n + q) * (n - 1);"),
+    ("packed_scale_dropped_in_exp", "y[k] = exp(scale * s[k] - m);\n                    l += y[k];\n                }\n                for (long long k = 0; k < n; ++k) y[k] /= l;",
+     "y[k] = exp(s[k] - m);\n                    l += y[k];\n                }\n                for (long long k = 0; k < n; ++k) y[k] /= l;"),
     ("merge_is_a_copy", "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];",
      "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * S + s) * H + h) * D + d];"),
 ]

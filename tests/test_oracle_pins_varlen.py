@@ -55,3 +55,47 @@ def test_varlen_layernorm_touches_only_real_rows():
     for bi, n in enumerate(lens):
         np.testing.assert_allclose(y[bi, :n], want[bi, :n], rtol=1e-11, atol=1e-13)
         assert (y[bi, n:] == -7.25).all()
+
+
+# ------------------------------------------------------------------ row-packed layout (no padding in memory)
+
+def _pack(blocks):
+    return np.concatenate([b.reshape(-1) for b in blocks])
+
+
+def test_packed_softmax_by_hand():
+    # two requests, one head: lengths 3 and 1.  Scores 0, 8 ln 2, 8 ln 3 at scale 1/8 weigh 1 : 2 : 3.
+    r0 = np.array([[0.0, 8 * np.log(2), 8 * np.log(3)], [1.0, 1.0, 1.0], [0.0, 8 * np.log(3), 0.0]])
+    r1 = np.array([[42.0]])
+    y = orc.masked_softmax_packed(_pack([r0, r1]), [3, 1], 1, 0.125)
+    np.testing.assert_allclose(y[0:3], [1 / 6, 1 / 3, 1 / 2], rtol=1e-14)
+    np.testing.assert_allclose(y[3:6], [1 / 3] * 3, rtol=1e-14)
+    np.testing.assert_allclose(y[6:9], [1 / 5, 3 / 5, 1 / 5], rtol=1e-14)
+    assert y[9] == 1.0 and y.size == 10
+
+
+def test_packed_softmax_equals_library_softmax_per_request_and_skips_empty_requests():
+    rng = np.random.default_rng(3)
+    H, lens = 3, [4, 0, 1, 7, 2]
+    blocks = [rng.normal(size=(H, n, n)) * 3 for n in lens]
+    y = orc.masked_softmax_packed(_pack(blocks), lens, H, 0.25)
+    pos = 0
+    for n, blk in zip(lens, blocks):
+        want = torch.softmax(torch.from_numpy(blk) * 0.25, -1).numpy()
+        np.testing.assert_allclose(y[pos:pos + H * n * n].reshape(H, n, n), want, rtol=1e-13)
+        pos += H * n * n
+    assert pos == y.size
+    with pytest.raises(ValueError):
+        orc.masked_softmax_packed(np.zeros(5), [2], 1, 1.0)
+
+
+def test_packed_softmax_is_the_padded_batch_without_its_padding():
+    """Packing is a change of layout only: the real part of the zero-padded batch, computed by the length-aware
+    oracle, is the packed result element for element."""
+    rng = np.random.default_rng(4)
+    B, H, S = 3, 2, 6
+    lens = np.array([6, 2, 5])
+    padded = rng.normal(size=(B, H, S, S)) * 2
+    y_pad = orc.masked_softmax_varlen(padded, lens, lens, 0.5)
+    y = orc.masked_softmax_packed(_pack([padded[b, :, :n, :n] for b, n in enumerate(lens)]), lens, H, 0.5)
+    np.testing.assert_array_equal(y, _pack([y_pad[b, :, :n, :n] for b, n in enumerate(lens)]))
