@@ -269,6 +269,28 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
         ms, _, _ = time_launches(torch, stream, fn, iters, per, launch)
         rows[name] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1),
                       "padded_bytes": padded_bytes, "real_fraction_of_padded_bytes": round(nbytes / padded_bytes, 3)}
+    # the same requests with no padding in memory at all (row-packed): softmax blocks [H, n, n] one after the other,
+    # LayerNorm over the [sum n, hidden] token rows with the ordinary entry point
+    cu, off = wl.packed_layout(spec.lengths, H)
+    total_tokens, n_scores = int(cu[-1]), int(off[-1])
+    n_sets = int(max(2, min(MAX_SETS, -(-COLD_BYTES // (es * n_scores)))))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.SEED_BASE + 2002)
+    packed = [torch.randn(n_scores, generator=gen, device="cuda") * spec.score_std for _ in range(n_sets)]
+    cu_d, off_d = torch.from_numpy(cu).cuda(), torch.from_numpy(off).cuda()
+    max_len = int(spec.lengths.max())
+    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_masked_softmax_packed(
+        packed[i % n_sets], cu_d, off_d, H, total_tokens, max_len, spec.scale, stream=stream), iters, n_sets, launch)
+    nbytes = 2 * es * n_scores + 12 * (B + 1)
+    rows["softmax_packed"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1)}
+    del packed
+    n_sets = int(max(2, min(MAX_SETS, -(-COLD_BYTES // (3 * es * total_tokens * hid)))))
+    xs, rs = ([torch.randn((total_tokens, hid), generator=gen, device="cuda") for _ in range(n_sets)] for _ in range(2))
+    outs = [torch.empty_like(x) for x in xs]
+    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_layernorm_dt(
+        xs[i % n_sets], rs[i % n_sets], ks.bias, ks.gamma, ks.beta, spec.eps, outs[i % n_sets], stream=stream), iters, n_sets, launch)
+    nbytes = 3 * es * total_tokens * hid + 3 * es * hid
+    rows["layernorm_packed"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1)}
     rows["lengths"] = [int(v) for v in spec.lengths]
     return rows
 

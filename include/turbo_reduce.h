@@ -97,6 +97,25 @@ int turbo_masked_softmax_varlen(void *scores, const int *q_lengths, const int *k
                                 float scale, int dtype, void *stream);
 
 /*
+ * Row-packed variant for variable-length batches that are not padded in memory at all (the paper pads, Sections
+ * 2.1 and 5; this is the layout its discussion of wasted padding work points to).  Request b, of len_b tokens,
+ * stores its self-attention scores as a dense [H][len_b][len_b] block; the blocks lie in `scores` at the element
+ * offsets score_offsets[b] (normally one after the other: score_offsets[b] = H * sum_{i<b} len_i^2).  In place:
+ *
+ *   for every request b, head h, query q < len_b:   row <- softmax over k < len_b of scale * row.
+ *
+ * cu_seqlens:    DEVICE int32 [B+1], cumulative lengths: cu_seqlens[0] = 0, cu_seqlens[b+1] - cu_seqlens[b] = len_b >= 0.
+ * score_offsets: DEVICE int64 [B+1] (entry B is not read).
+ * total_tokens:  the caller's HOST copy of cu_seqlens[B] (sizes the launch);  max_len: HOST upper bound on len_b
+ *                (sizes the registers per row); a request longer than max_len is left untouched.
+ * One wavefront holds one row, so max_len is at most 4096 (TURBO_F32) or 8192 (TURBO_F16) (TURBO_ERR_SHAPE beyond).
+ * The LayerNorm of a packed batch needs no entry point of its own: its tokens are [total_tokens, hidden] rows of
+ * turbo_add_bias_layernorm_dt.
+ */
+int turbo_masked_softmax_packed(void *scores, const int *cu_seqlens, const long long *score_offsets, int B, int H,
+                                int total_tokens, int max_len, float scale, int dtype, void *stream);
+
+/*
  * Fused bias add + residual add + LayerNorm (the "AddBiasLayerNorm" kernel of
  * Section 6.2.1; Section 4.1.2 and Equation 1: LayerNorm reduces a mean and a
  * population variance per row), binary32 tensors:

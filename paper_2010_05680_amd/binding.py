@@ -24,7 +24,7 @@ TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES = 0, 1, 2
 PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
-    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_add_bias_layernorm",
+    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_masked_softmax_packed", "turbo_add_bias_layernorm",
     "turbo_add_bias_layernorm_dt", "turbo_add_bias_layernorm_varlen",
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
     "turbo_batch_schedule", "turbo_mem_plan", "turbo_cost_table_fill",
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.turbo_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
         L.turbo_debug_fastdiv.restype = ctypes.c_uint
         L.turbo_stream_probe.argtypes = [vp, vp, vp, ctypes.c_longlong, vp]
+        L.turbo_masked_softmax_packed.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp]
+        L.turbo_masked_softmax_packed.restype = i
         L.turbo_stream_probe.restype = i
         _lib = L
     return _lib
@@ -169,6 +171,21 @@ def _layernorm_args(x, residual, bias, gamma, beta, out):
         if t is not None and (tuple(t.shape) != shape or t.dtype != x.dtype):
             raise ValueError(f"{name} must be {shape} in x's dtype")
     return rows, hidden
+
+
+def turbo_masked_softmax_packed(scores: torch.Tensor, cu_seqlens: torch.Tensor, score_offsets: torch.Tensor, H: int,
+                                total_tokens: int, max_len: int, scale: float, stream=None) -> torch.Tensor:
+    """In-place softmax over a row-packed batch: `scores` is flat, request b's [H, len_b, len_b] block starts at
+    score_offsets[b]; cu_seqlens (int32 [B+1]) and score_offsets (int64 [B+1]) live on the device."""
+    dt = _dtype_code(scores)
+    if cu_seqlens.dtype != torch.int32 or score_offsets.dtype != torch.int64 or cu_seqlens.numel() != score_offsets.numel():
+        raise ValueError("cu_seqlens must be int32 [B+1] and score_offsets int64 [B+1]")
+    B = cu_seqlens.numel() - 1
+    _check(lib().turbo_masked_softmax_packed(_dev_ptr(scores, "scores"), _dev_ptr(cu_seqlens, "cu_seqlens"),
+                                             _dev_ptr(score_offsets, "score_offsets"), B, int(H), int(total_tokens),
+                                             int(max_len), float(scale), dt, _stream_ptr(stream)),
+           "turbo_masked_softmax_packed")
+    return scores
 
 
 def turbo_add_bias_layernorm(x, residual, bias, gamma, beta, eps: float, out: torch.Tensor, stream=None) -> torch.Tensor:

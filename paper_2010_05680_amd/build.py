@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libturbo_reduce.so")
 
-SOURCES = ["api.hip", "softmax_f32.hip", "softmax_f16.hip", "layernorm_f32.hip", "layernorm_f16.hip", "elementwise.hip",
+SOURCES = ["api.hip", "softmax_f32.hip", "softmax_f16.hip", "layernorm_f32.hip", "layernorm_f16.hip", "elementwise.hip", "packed.hip",
            "serving_host.cpp"]
 
 HIPCC_FLAGS = [

@@ -9,6 +9,7 @@
 #include "../../include/turbo_reduce.h"
 #include "elementwise_kernels.h"
 #include "layernorm_kernels.h"
+#include "packed_kernels.h"
 #include "plan.h"
 #include "softmax_kernels.h"
 
@@ -285,6 +286,29 @@ int turbo_add_bias_layernorm_varlen(const void* x, const void* residual, const v
     if (B <= 0 || S <= 0 || (long long)B * S > kMaxRows) return TURBO_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(lengths) % 4 != 0) return TURBO_ERR_ALIGN;
     return layernorm_impl(x, residual, bias, gamma, beta, B * S, hidden, eps, out, dtype, stream, lengths, S);
+}
+
+int turbo_masked_softmax_packed(void* scores, const int* cu_seqlens, const long long* score_offsets, int B, int H,
+                                int total_tokens, int max_len, float scale, int dtype, void* stream) {
+    if (scores == nullptr || cu_seqlens == nullptr || score_offsets == nullptr) return TURBO_ERR_NULL;
+    const int es = elem_size_of(dtype);
+    if (es == 0) return TURBO_ERR_DTYPE;
+    if (B <= 0 || H <= 0 || total_tokens <= 0 || max_len <= 0 || max_len > total_tokens) return TURBO_ERR_SHAPE;
+    if ((long long)H * total_tokens > kMaxRows) return TURBO_ERR_SHAPE;
+    if (max_len > 64 * 16 * (16 / es)) return TURBO_ERR_SHAPE;  // one wavefront holds a row: 16 vectors per lane at most
+    if (reinterpret_cast<uintptr_t>(scores) % es != 0 || reinterpret_cast<uintptr_t>(cu_seqlens) % 4 != 0 ||
+        reinterpret_cast<uintptr_t>(score_offsets) % 8 != 0)
+        return TURBO_ERR_ALIGN;
+    turbo::PackedSoftmaxArgs a;
+    a.scores = scores;
+    a.cu_seqlens = cu_seqlens;
+    a.score_offsets = score_offsets;
+    a.B = B;
+    a.H = H;
+    a.n_rows = H * total_tokens;
+    a.scale = scale;
+    const hipError_t err = turbo::launch_softmax_packed(a, es, max_len, reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }
 
 const char* turbo_status_string(int status) {

@@ -127,6 +127,15 @@ def config_spec(index: int, seed_base: int = SEED_BASE) -> ConfigSpec:
     raise ValueError(f"no such config: {index}")
 
 
+def packed_layout(lengths, H: int):
+    """Row-packed batch: (cu_seqlens int32 [B+1], score_offsets int64 [B+1]); request b's [H, len_b, len_b] scores
+    start at element score_offsets[b], score_offsets[B] is the total."""
+    n = np.asarray(lengths, dtype=np.int64)
+    cu = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(int(H) * n * n)]).astype(np.int64)
+    return cu, off
+
+
 def key_mask_from_lengths(lengths: np.ndarray, Sk: int, dtype) -> np.ndarray:
     """[B, Sk] additive key mask: 0 for k < len_b, MASK_VALUE beyond."""
     k = np.arange(Sk)[None, :]

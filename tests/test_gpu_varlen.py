@@ -150,3 +150,93 @@ def test_varlen_error_paths():
         == tb.TURBO_ERR_NULL
     assert L.turbo_add_bias_layernorm_varlen(fake, fake, fake, fake, fake, fake, 0, 4, 8, 1e-5, fake, tb.TURBO_F32, None) \
         == tb.TURBO_ERR_SHAPE
+
+
+# ------------------------------------------------------------------ row-packed layout (no padding in memory)
+
+def _run_packed(blocks_flat, lengths, H, scale, dtype, max_len=None, lead=0, tail=0):
+    """Upload the flat packed scores into a buffer with `lead`/`tail` guard elements, run, return (result, buffer)."""
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    cu, off = wl.packed_layout(lengths, H)
+    n = blocks_flat.size
+    buf = torch.full((lead + n + tail,), float("nan"), dtype=tdt, device="cuda")
+    view = buf[lead:lead + n]
+    view.copy_(torch.from_numpy(blocks_flat))
+    tb.turbo_masked_softmax_packed(view, torch.from_numpy(cu).cuda(), torch.from_numpy(off).cuda(), H, int(cu[-1]),
+                                   int(max(lengths)) if max_len is None else max_len, scale)
+    torch.cuda.synchronize()
+    return _np(view), buf
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_packed_softmax_shapes(dtype):
+    rng = np.random.Generator(np.random.Philox(31))
+    cases = [([1], 1), ([5], 2), ([3, 0, 1, 2], 3), ([8, 63, 64, 65], 2), ([100, 7, 257, 31, 4], 3), ([493, 5, 128, 500, 17], 12),
+             ([1000, 3], 1), ([2049, 40], 1), ([4096, 9, 4095], 1),
+             ([3, 1, 4, 1, 5, 9, 2, 6, 0] * 7, 2), ([3, 1, 4, 1, 5, 9, 2, 6] * 9, 2)]  # 63 and 72 requests: both table look-ups
+    if dtype == F16:
+        cases.append(([8192, 11, 5000], 1))
+    for lengths, H in cases:
+        total = H * sum(n * n for n in lengths)
+        flat = (rng.standard_normal(total, dtype=np.float32) * 3).astype(dtype)
+        for lead in (0, 3):  # row starts are only element-aligned either way; an odd base pointer on top
+            got, buf = _run_packed(flat, lengths, H, 0.125, dtype, lead=lead, tail=16)
+            want = orc.masked_softmax_packed(flat, lengths, H, 0.125)
+            assert_parity(got, want, dtype, f"packed softmax lengths={lengths} H={H} lead={lead}")
+            assert torch.isnan(buf[:lead]).all() and torch.isnan(buf[lead + total:]).all(), "wrote outside the batch"
+
+
+def test_packed_softmax_max_len_is_an_upper_bound_and_longer_requests_are_left_alone():
+    rng = np.random.Generator(np.random.Philox(32))
+    lengths, H = [40, 300, 9], 2
+    total = H * sum(n * n for n in lengths)
+    flat = rng.standard_normal(total, dtype=np.float32) * 3
+    want = orc.masked_softmax_packed(flat, lengths, H, 0.5)
+    got, _ = _run_packed(flat, lengths, H, 0.5, F32, max_len=349)       # any bound >= the longest request
+    assert_parity(got, want, F32, "packed softmax with a loose max_len")
+    got, _ = _run_packed(flat, lengths, H, 0.5, F32, max_len=256)       # request 1 does not fit 256 keys per row
+    _, off = wl.packed_layout(lengths, H)
+    np.testing.assert_array_equal(got[off[1]:off[2]], flat[off[1]:off[2]])
+    assert_parity(got[:off[1]], want[:off[1]], F32, "request 0")
+    assert_parity(got[off[2]:], want[off[2]:], F32, "request 2")
+
+
+def test_packed_softmax_config_2_lengths_match_the_padded_length_aware_kernel():
+    """Config 2's 32 requests, packed: the same numbers as the padded batch gives on its real part."""
+    spec = wl.config_spec(2)
+    lengths = [int(v) for v in spec.lengths]
+    case = wl.softmax_case(spec)
+    flat = np.concatenate([case.scores[b, :, :n, :n].reshape(-1) for b, n in enumerate(lengths)])
+    got, _ = _run_packed(flat, lengths, spec.H, spec.scale, F32)
+    _, off = wl.packed_layout(lengths, spec.H)
+    for b in (0, 8, 23, 31):  # the oracle on a few whole requests (the longest, the shortest, two others)
+        n = lengths[b]
+        want = orc.masked_softmax_packed(flat[off[b]:off[b + 1]], [n], spec.H, spec.scale)
+        assert_parity(got[off[b]:off[b + 1]], want, F32, f"packed config 2, request {b} of {n} tokens")
+    sums = np.add.reduceat(got.astype(np.float64), np.concatenate(
+        [off[b] + np.arange(spec.H * n) * n for b, n in enumerate(lengths)]))
+    assert np.abs(sums - 1).max() < 1e-5
+
+
+def test_packed_layernorm_is_the_plain_kernel_on_the_packed_tokens():
+    rng = np.random.Generator(np.random.Philox(33))
+    lengths, hidden = [17, 1, 300, 45], 768
+    total = sum(lengths)
+    case = wl.random_layernorm_case(34, total, hidden, eps=1e-5)
+    assert_parity(_np(gu.run_layernorm(case)), gu.oracle_layernorm(case), F32, "LayerNorm over the packed tokens")
+
+
+def test_packed_error_paths():
+    # every call below must be rejected by the host-side validation: the pointers are not real
+    L = tb.lib()
+    fake = 0x10000
+    f = L.turbo_masked_softmax_packed
+    assert f(None, fake, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert f(fake, None, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert f(fake, fake, fake, 0, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert f(fake, fake, fake, 1, 1, 4, 5, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE     # max_len > total_tokens
+    assert f(fake, fake, fake, 1, 1, 5000, 4097, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # beyond one wavefront
+    assert f(fake, fake, fake, 1, 1, 9000, 8193, 1.0, tb.TURBO_F16, None) == tb.TURBO_ERR_SHAPE
+    assert f(fake, fake + 2, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert f(fake, fake, fake + 4, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert f(fake, fake, fake, 1, 1, 4, 4, 1.0, 9, None) == tb.TURBO_ERR_DTYPE
