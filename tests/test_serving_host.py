@@ -316,3 +316,18 @@ def test_allocator_rejects_bad_input():
         sv.turbo_mem_plan([0], [1], [10], [], k_scale=0.5)
     with pytest.raises(tb.TurboError):
         sv.turbo_mem_plan([0, 0], [1, 1], [10, 10], [], default_chunk_size=10, k_scale=1.0, max_chunks=1)
+
+
+def test_host_routines_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """Compiles the host-side C++ with -fsanitize=address,undefined into a small driver (tests/native/) that runs
+    random instances, rejected ones included, with output arrays of exactly the documented sizes."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "host_sanitize"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-static-libubsan",  # the runtimes inside the program: no load-order demands
+                           os.path.join(root, "tests", "native", "host_sanitize.cpp"),
+                           os.path.join(root, "paper_2010_05680_amd", "csrc", "serving_host.cpp"), "-o", str(exe)])
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and res.stdout.strip() == "ok", res.stdout + res.stderr
