@@ -134,7 +134,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         }
     }
     p.vec = vec;
-    const long long nvec = (row_len + vec - 1) / vec;
+    const long long nvec = ((long long)row_len + vec - 1) / vec;
 
     // wave family: feasible when one wavefront's registers hold the row
     bool wave_ok = false;

@@ -218,3 +218,15 @@ def test_no_kernel_of_the_built_library_spills_registers():
     assert len(lines) > 100
     bad = [ln[0] for ln in lines if "scratch=0" not in ln or "vgpr_spill=0" not in ln]
     assert bad == []
+
+
+def test_planner_under_sanitizers_with_row_lengths_up_to_int_max(tmp_path):
+    """csrc/plan.h is host code: compiled alone with -fsanitize=address,undefined and driven over every element size,
+    alignment, override and row lengths up to INT_MAX (tests/native/plan_sanitize.cpp checks the shape invariants)."""
+    import subprocess
+    exe = tmp_path / "plan_sanitize"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-static-libubsan", os.path.join(ROOT, "tests", "native", "plan_sanitize.cpp"),
+                           "-o", str(exe)])
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and res.stdout.startswith("ok"), res.stdout + res.stderr
