@@ -71,8 +71,9 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
     const int es = elem_size_of(dtype);
     if (es == 0) return TURBO_ERR_DTYPE;
     if (B <= 0 || H <= 0 || Sq <= 0 || Sk <= 0) return TURBO_ERR_SHAPE;
-    const long long n_rows = (long long)B * H * Sq;
-    if ((long long)H * Sq > kMaxRows || n_rows > kMaxRows) return TURBO_ERR_SHAPE;
+    const long long rows_per_batch = (long long)H * Sq;  // two 31-bit factors: fits
+    if (rows_per_batch > kMaxRows || rows_per_batch * B > kMaxRows) return TURBO_ERR_SHAPE;  // <= 2^31 * 2^31
+    const long long n_rows = rows_per_batch * B;
     if (mask != nullptr && (msb < 0 || msq < 0)) return TURBO_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(scores) % es != 0) return TURBO_ERR_ALIGN;
     if (mask != nullptr && reinterpret_cast<uintptr_t>(mask) % es != 0) return TURBO_ERR_ALIGN;
@@ -194,8 +195,11 @@ int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, 
     const int es = elem_size_of(dtype);
     if (es == 0) return TURBO_ERR_DTYPE;
     if (B <= 0 || N1 <= 0 || K <= 0 || N2 <= 0 || D <= 0) return TURBO_ERR_SHAPE;
-    const long long total = (long long)B * N1 * K * N2 * D;
-    if (total / D != (long long)B * N1 * K * N2 || total > (1ll << 40)) return TURBO_ERR_SHAPE;
+    long long total = 1;  // B*N1*K*N2*D, at most 2^40 elements; checked factor by factor so nothing overflows
+    for (const int dim : {B, N1, K, N2, D}) {
+        if (total > (1ll << 40) / dim) return TURBO_ERR_SHAPE;
+        total *= dim;
+    }
     long long align_elems = 16;
     for (const void* p : {x, bias, (const void*)out}) {
         if (p == nullptr) continue;

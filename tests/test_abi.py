@@ -47,6 +47,8 @@ def test_softmax_rejects_bad_arguments_without_a_gpu():
     for dims in [(0, 1, 4, 4), (1, 0, 4, 4), (1, 1, 0, 4), (1, 1, 4, 0), (-1, 1, 4, 4), (1, 1, 4, -3)]:
         assert f(FAKE, None, *dims, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert f(FAKE, None, 1 << 15, 1 << 15, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # 2^32 rows
+    big = 2 ** 31 - 1
+    assert f(FAKE, None, big, big, big, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # no overflow on the way
     assert f(FAKE + 2, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert f(FAKE + 1, None, 1, 1, 4, 4, 1.0, tb.TURBO_F16, None) == tb.TURBO_ERR_ALIGN
     assert f(FAKE, FAKE + 0x1002, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN

@@ -157,6 +157,9 @@ def test_elementwise_error_paths_need_no_gpu_work():
     assert L.turbo_add_bias_gelu(fake + 2, None, 4, 4, 0, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert L.turbo_add_bias_split_heads(fake, None, 1, 1, 0, 1, 1, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert L.turbo_merge_heads(fake, 1, 1, 1, 1, None, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    big = 2 ** 31 - 1  # the element count is checked factor by factor: no overflow on the way to the verdict
+    assert L.turbo_add_bias_split_heads(fake, None, big, big, big, big, big, fake, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_merge_heads(fake, big, big, big, 4, fake, tb.TURBO_F16, None) == tb.TURBO_ERR_SHAPE
 
 
 def test_stream_probe_copies_and_adds():
