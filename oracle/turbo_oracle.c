@@ -249,6 +249,37 @@ void oracle_masked_softmax_varlen(const double *scores, const int *q_len, const 
     }
 }
 
+/* Causal variant: query q sees the keys k <= q + (Sk - Sq) (the last query sees every key), further restricted to
+ * k < k_len[b] when k_len is given.  Rows with q >= q_len[b] (when q_len is given) and rows without any visible key
+ * are copied unchanged; everywhere else the visible keys get softmax(scale * s) and the others exact zeros. */
+void oracle_masked_softmax_causal(const double *scores, const int *q_len, const int *k_len, int B, int H, int Sq, int Sk,
+                                  double scale, double *out)
+{
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int q = 0; q < Sq; ++q) {
+                long long row = ((long long)b * H + h) * Sq + q;
+                const double *s = scores + row * Sk;
+                double *y = out + row * Sk;
+                int visible = q + (Sk - Sq) + 1;          /* keys 0 .. q + (Sk - Sq) */
+                if (k_len != NULL && k_len[b] < visible) visible = k_len[b];
+                if (visible > Sk) visible = Sk;
+                if (visible <= 0 || (q_len != NULL && q >= q_len[b])) {
+                    for (int k = 0; k < Sk; ++k) y[k] = s[k];
+                    continue;
+                }
+                double m = -INFINITY, l = 0.0;
+                for (int k = 0; k < visible; ++k)
+                    if (scale * s[k] > m) m = scale * s[k];
+                for (int k = 0; k < visible; ++k) {
+                    y[k] = exp(scale * s[k] - m);
+                    l += y[k];
+                }
+                for (int k = 0; k < visible; ++k) y[k] /= l;
+                for (int k = visible; k < Sk; ++k) y[k] = 0.0;
+            }
+}
+
 /* Row-packed variable-length batch: no padding in memory.  Request b holds its scores as [H][len_b][len_b],
  * the requests follow one another (request b starts at element H * sum_{i<b} len_i^2).  Every row of len_b keys is
  * normalised: y = softmax(scale * s) over the row.  `scores` and `out` hold H * sum len_b^2 values. */

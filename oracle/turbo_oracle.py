@@ -58,6 +58,9 @@ def _load():
         lib.oracle_masked_softmax_varlen.argtypes = [_dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                      ctypes.c_int, ctypes.c_double, _dp]
         lib.oracle_masked_softmax_varlen.restype = None
+        lib.oracle_masked_softmax_causal.argtypes = [_dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_double, _dp]
+        lib.oracle_masked_softmax_causal.restype = None
         lib.oracle_masked_softmax_packed.argtypes = [_dp, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_double, _dp]
         lib.oracle_masked_softmax_packed.restype = None
         lib.oracle_add_bias_layernorm_varlen.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int,
@@ -217,6 +220,21 @@ def masked_softmax_varlen(scores, q_lengths, k_lengths, scale: float = 1.0) -> n
     out = np.empty_like(s)
     if s.size:
         _load().oracle_masked_softmax_varlen(_ptr(s), _iptr(ql), _iptr(kl), B, H, Sq, Sk, float(scale), _ptr(out))
+    return out
+
+
+def masked_softmax_causal(scores, q_lengths, k_lengths, scale: float = 1.0) -> np.ndarray:
+    """Causal softmax on [B,H,Sq,Sk]: query q sees keys k <= q + (Sk - Sq), and k < k_lengths[b] if given; rows
+    q >= q_lengths[b] (if given) and rows without a visible key are returned unchanged."""
+    s = _f64(scores)
+    B, H, Sq, Sk = s.shape
+    kl = None if k_lengths is None else _i32(k_lengths)
+    ql = None if q_lengths is None else _i32(q_lengths)
+    if (kl is not None and kl.shape != (B,)) or (ql is not None and ql.shape != (B,)):
+        raise ValueError("lengths must be [B]")
+    out = np.empty_like(s)
+    if s.size:
+        _load().oracle_masked_softmax_causal(_ptr(s), _iptr(ql), _iptr(kl), B, H, Sq, Sk, float(scale), _ptr(out))
     return out
 
 

@@ -50,6 +50,9 @@ MUTATIONS = [
     ("packed_row_stride_wrong", "const double *s = scores + base + (h * n + q) * n;", "const double *s = scores + base + (h * n + q) * (n - 1);"),
     ("packed_scale_dropped_in_exp", "y[k] = exp(scale * s[k] - m);\n                    l += y[k];\n                }\n                for (long long k = 0; k < n; ++k) y[k] /= l;",
      "y[k] = exp(s[k] - m);\n                    l += y[k];\n                }\n                for (long long k = 0; k < n; ++k) y[k] /= l;"),
+    ("causal_diagonal_off_by_one", "int visible = q + (Sk - Sq) + 1;", "int visible = q + (Sk - Sq);"),
+    ("causal_offset_sign", "int visible = q + (Sk - Sq) + 1;", "int visible = q - (Sk - Sq) + 1;"),
+    ("causal_ignores_key_lengths", "if (k_len != NULL && k_len[b] < visible) visible = k_len[b];", ""),
     ("merge_is_a_copy", "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * H + h) * S + s) * D + d];",
      "out[(((long long)b * S + s) * H + h) * D + d] = x[(((long long)b * S + s) * H + h) * D + d];"),
 ]

@@ -99,3 +99,59 @@ def test_packed_softmax_is_the_padded_batch_without_its_padding():
     y_pad = orc.masked_softmax_varlen(padded, lens, lens, 0.5)
     y = orc.masked_softmax_packed(_pack([padded[b, :, :n, :n] for b, n in enumerate(lens)]), lens, H, 0.5)
     np.testing.assert_array_equal(y, _pack([y_pad[b, :, :n, :n] for b, n in enumerate(lens)]))
+
+
+# ------------------------------------------------------------------ causal variant
+
+def test_causal_softmax_by_hand():
+    # 3 queries over 3 keys: row q sees keys 0..q.  Scores 0, 8 ln 2, 8 ln 3 at scale 1/8 weigh 1 : 2 : 3.
+    row = [0.0, 8 * np.log(2), 8 * np.log(3)]
+    s = np.array([row, row, row]).reshape(1, 1, 3, 3)
+    y = orc.masked_softmax_causal(s, None, None, 0.125)[0, 0]
+    np.testing.assert_allclose(y[0], [1.0, 0.0, 0.0], rtol=1e-14)
+    np.testing.assert_allclose(y[1], [1 / 3, 2 / 3, 0.0], rtol=1e-14)
+    np.testing.assert_allclose(y[2], [1 / 6, 1 / 3, 1 / 2], rtol=1e-14)
+    assert y[0, 1] == 0.0 and y[0, 2] == 0.0 and y[1, 2] == 0.0
+    # more keys than queries (a cache of 2 earlier keys): the diagonal moves right by Sk - Sq, the last query sees all
+    s = np.zeros((1, 1, 2, 4))
+    y = orc.masked_softmax_causal(s, None, None, 1.0)[0, 0]
+    np.testing.assert_allclose(y, [[1 / 3, 1 / 3, 1 / 3, 0.0], [0.25] * 4], rtol=1e-14)
+    # more queries than keys: the first Sq - Sk queries see nothing and are left alone
+    s = np.arange(6.0).reshape(1, 1, 3, 2)
+    y = orc.masked_softmax_causal(s, None, None, 1.0)[0, 0]
+    np.testing.assert_array_equal(y[0], s[0, 0, 0])
+    np.testing.assert_allclose(y[1], [1.0, 0.0])
+    assert y[2].sum() == pytest.approx(1.0) and (y[2] > 0).all()
+
+
+@pytest.mark.parametrize("Sq,Sk", [(7, 7), (5, 9), (12, 12)])
+def test_causal_softmax_equals_library_softmax_under_a_triangular_mask(Sq, Sk):
+    rng = np.random.default_rng(Sq * 100 + Sk)
+    B, H = 3, 2
+    s = rng.normal(size=(B, H, Sq, Sk)) * 3
+    y = orc.masked_softmax_causal(s, None, None, 0.3)
+    keep = torch.ones(Sq, Sk, dtype=torch.bool).tril(diagonal=Sk - Sq)
+    z = (torch.from_numpy(s) * 0.3).masked_fill(~keep, float("-inf"))
+    np.testing.assert_allclose(y, torch.softmax(z, -1).numpy(), rtol=1e-13)
+    assert (y[..., ~keep.numpy()] == 0).all()
+    # the padded formulation with an additive 0 / -10000 mask above the diagonal gives the same weights (square case)
+    if Sq == Sk:
+        padded = orc.masked_softmax(s, wl.causal_mask(Sq, Sk, np.float64), 0, Sk, 0.3)
+        np.testing.assert_allclose(y, padded, rtol=1e-12, atol=1e-300)
+
+
+def test_causal_softmax_with_request_lengths():
+    rng = np.random.default_rng(9)
+    B, H, S = 3, 2, 8
+    s = rng.normal(size=(B, H, S, S))
+    k_len, q_len = np.array([8, 3, 5]), np.array([8, 8, 4])
+    y = orc.masked_softmax_causal(s, q_len, k_len, 1.0)
+    for b in range(B):
+        for q in range(S):
+            if q >= q_len[b]:
+                np.testing.assert_array_equal(y[b, :, q], s[b, :, q])
+                continue
+            n = min(q + 1, k_len[b])
+            want = torch.softmax(torch.from_numpy(s[b, :, q, :n]), -1).numpy()
+            np.testing.assert_allclose(y[b, :, q, :n], want, rtol=1e-13)
+            assert (y[b, :, q, n:] == 0).all()
