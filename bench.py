@@ -292,6 +292,19 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
     nbytes = 3 * es * total_tokens * hid + 3 * es * hid
     rows["layernorm_packed"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1)}
     rows["lengths"] = [int(v) for v in spec.lengths]
+    del ks, xs, rs, outs
+    torch.cuda.empty_cache()
+    # config 4 (GPT-2-medium, fp16) through the causal entry point: no mask tensor, keys above the diagonal unread
+    spec4 = wl.config_spec(4)
+    k4 = KernelSets(spec4, torch, tb, wl)
+    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_masked_softmax_causal(k4.scores[i % k4.n_sm_sets], None, None,
+                                                                                  spec4.scale, stream=stream),
+                             iters, k4.n_sm_sets, launch)
+    n_rows, Sq, Sk = spec4.B * spec4.H * spec4.Sq, spec4.Sq, spec4.Sk
+    read_elems = spec4.B * spec4.H * sum(min(Sk, -(-(q + 1 + Sk - Sq) // 8) * 8) for q in range(Sq))  # whole 16-byte vectors
+    nbytes = 2 * (read_elems + n_rows * Sk)
+    rows["causal_config4"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1),
+                              "additive_mask_bytes": k4.softmax_bytes}
     return rows
 
 

@@ -97,6 +97,18 @@ int turbo_masked_softmax_varlen(void *scores, const int *q_lengths, const int *k
                                 float scale, int dtype, void *stream);
 
 /*
+ * Causal variant of the length-aware call (decoder self-attention, e.g. the GPT-2 configuration of the benchmark):
+ * query q sees the keys k <= q + (Sk - Sq), so with Sq == Sk the usual lower triangle and with a key cache
+ * (Sk > Sq) the last query sees every key.  The keys beyond the diagonal get weight exactly 0 WITHOUT BEING READ,
+ * which halves the bytes read for a square score matrix; this equals turbo_masked_softmax_ex with a 0 / -10000
+ * mask above the diagonal.  q_lengths and k_lengths (DEVICE int32 [B]) restrict rows and keys further as in
+ * turbo_masked_softmax_varlen; either may be NULL.  Rows that see no key (Sq > Sk, or a zero length) are left
+ * untouched.
+ */
+int turbo_masked_softmax_causal(void *scores, const int *q_lengths, const int *k_lengths, int B, int H, int Sq, int Sk,
+                                float scale, int dtype, void *stream);
+
+/*
  * Row-packed variant for variable-length batches that are not padded in memory at all (the paper pads, Sections
  * 2.1 and 5; this is the layout its discussion of wasted padding work points to).  Request b, of len_b tokens,
  * stores its self-attention scores as a dense [H][len_b][len_b] block; the blocks lie in `scores` at the element

@@ -24,7 +24,7 @@ TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES = 0, 1, 2
 PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
-    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_masked_softmax_packed", "turbo_add_bias_layernorm",
+    "turbo_masked_softmax", "turbo_masked_softmax_ex", "turbo_masked_softmax_varlen", "turbo_masked_softmax_packed", "turbo_masked_softmax_causal", "turbo_add_bias_layernorm",
     "turbo_add_bias_layernorm_dt", "turbo_add_bias_layernorm_varlen",
     "turbo_add_bias_gelu", "turbo_add_bias_split_heads", "turbo_merge_heads",
     "turbo_batch_schedule", "turbo_mem_plan", "turbo_cost_table_fill",
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.turbo_stream_probe.argtypes = [vp, vp, vp, ctypes.c_longlong, vp]
         L.turbo_masked_softmax_packed.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp]
         L.turbo_masked_softmax_packed.restype = i
+        L.turbo_masked_softmax_causal.argtypes = L.turbo_masked_softmax_varlen.argtypes
+        L.turbo_masked_softmax_causal.restype = i
         L.turbo_stream_probe.restype = i
         _lib = L
     return _lib
@@ -160,6 +162,18 @@ def turbo_masked_softmax_varlen(scores: torch.Tensor, q_lengths: Optional[torch.
     _check(lib().turbo_masked_softmax_varlen(_dev_ptr(scores, "scores"), _lengths_ptr(q_lengths, B, "q_lengths"),
                                              _lengths_ptr(k_lengths, B, "k_lengths"), B, H, Sq, Sk, float(scale), dt,
                                              _stream_ptr(stream)), "turbo_masked_softmax_varlen")
+    return scores
+
+
+def turbo_masked_softmax_causal(scores: torch.Tensor, q_lengths: Optional[torch.Tensor], k_lengths: Optional[torch.Tensor],
+                                scale: float, stream=None) -> torch.Tensor:
+    """In-place causal softmax: query q sees keys k <= q + (Sk - Sq), further limited by the optional lengths; the
+    other keys get weight 0 unread."""
+    B, H, Sq, Sk = scores.shape
+    dt = _dtype_code(scores)
+    _check(lib().turbo_masked_softmax_causal(_dev_ptr(scores, "scores"), _lengths_ptr(q_lengths, B, "q_lengths"),
+                                             _lengths_ptr(k_lengths, B, "k_lengths"), B, H, Sq, Sk, float(scale), dt,
+                                             _stream_ptr(stream)), "turbo_masked_softmax_causal")
     return scores
 
 

@@ -66,7 +66,8 @@ turbo::LaunchCfg launch_cfg(int num_cus) {
 }
 
 int softmax_impl(void* scores, const void* mask, long long msb, long long msq, const int* q_lengths,
-                 const int* k_lengths, int B, int H, int Sq, int Sk, float scale, int dtype, void* stream) {
+                 const int* k_lengths, int B, int H, int Sq, int Sk, float scale, int dtype, void* stream,
+                 int causal = 0) {
     if (scores == nullptr) return TURBO_ERR_NULL;
     const int es = elem_size_of(dtype);
     if (es == 0) return TURBO_ERR_DTYPE;
@@ -85,7 +86,7 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
         align_elems = min_ll(align_elems, stride_alignment(msq));
     }
     turbo::Overrides ovr = g_ovr;
-    if (k_lengths != nullptr) {
+    if (k_lengths != nullptr || q_lengths != nullptr || causal) {  // per-row key counts: the kernels need their bounds checks
         if (reinterpret_cast<uintptr_t>(k_lengths) % 4 != 0 || reinterpret_cast<uintptr_t>(q_lengths) % 4 != 0)
             return TURBO_ERR_ALIGN;
         ovr.no_full = 1;
@@ -97,6 +98,7 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
     a.mask = mask;
     a.k_lengths = k_lengths;
     a.q_lengths = q_lengths;
+    a.causal = causal;
     a.mask_stride_b = msb;
     a.mask_stride_q = msq;
     a.n_rows = (int)n_rows;
@@ -270,6 +272,11 @@ int turbo_masked_softmax_varlen(void* scores, const int* q_lengths, const int* k
                                 float scale, int dtype, void* stream) {
     if (k_lengths == nullptr) return TURBO_ERR_NULL;
     return softmax_impl(scores, nullptr, 0, 0, q_lengths, k_lengths, B, H, Sq, Sk, scale, dtype, stream);
+}
+
+int turbo_masked_softmax_causal(void* scores, const int* q_lengths, const int* k_lengths, int B, int H, int Sq, int Sk,
+                                float scale, int dtype, void* stream) {
+    return softmax_impl(scores, nullptr, 0, 0, q_lengths, k_lengths, B, H, Sq, Sk, scale, dtype, stream, 1);
 }
 
 int turbo_add_bias_layernorm(const void* x, const void* residual, const void* bias, const void* gamma,

@@ -23,7 +23,8 @@ namespace turbo {
 //   kMaskAdditive : an additive mask tensor is added to the scaled scores
 //   kMaskLengths  : per-request lengths: keys k >= k_len[b] get weight exactly 0 without being read, and rows
 //                   q >= q_len[b] are skipped altogether (the variable-length batches of Section 2.1, without
-//                   the cost of their zero padding)
+//                   the cost of their zero padding); optionally causal: keys beyond the query's diagonal are
+//                   treated the same way
 enum MaskKind { kMaskNone = 0, kMaskAdditive = 1, kMaskLengths = 2 };
 
 struct SoftmaxArgs {
@@ -31,8 +32,9 @@ struct SoftmaxArgs {
     const void* mask;
     long long mask_stride_b;
     long long mask_stride_q;
-    const int* k_lengths;  // kMaskLengths: [B] valid keys per request
+    const int* k_lengths;  // kMaskLengths: [B] valid keys per request, or null = all Sk keys
     const int* q_lengths;  // kMaskLengths: [B] valid query rows per request, or null = all rows
+    int causal;            // kMaskLengths: 1 = query q also sees only the keys k <= q + (Sk - Sq)
     int n_rows;      // B*H*Sq
     int Sq;
     int Sk;
@@ -63,11 +65,15 @@ constexpr int rows_in_flight_c(int nv, int vec, int target) {
 // kMaskLengths: number of valid keys of `row` (clamped to 0..Sk); 0 also for rows that are skipped.
 __device__ __forceinline__ int row_key_count(const SoftmaxArgs& a, int row) {
     const unsigned b = fastdiv((unsigned)row, a.div_rows_per_batch);
-    int klen = a.k_lengths[b];
+    int klen = a.k_lengths != nullptr ? a.k_lengths[b] : a.Sk;
     klen = klen < 0 ? 0 : (klen > a.Sk ? a.Sk : klen);
-    if (a.q_lengths != nullptr) {
+    if (a.q_lengths != nullptr || a.causal) {
         const int q = (int)((unsigned)row - fastdiv((unsigned)row, a.div_sq) * (unsigned)a.Sq);
-        if (q >= a.q_lengths[b]) klen = 0;
+        if (a.causal) {
+            const int visible = q + (a.Sk - a.Sq) + 1;  // may be <= 0 when there are more queries than keys
+            klen = visible < klen ? (visible < 0 ? 0 : visible) : klen;
+        }
+        if (a.q_lengths != nullptr && q >= a.q_lengths[b]) klen = 0;
     }
     return klen;
 }
@@ -537,7 +543,7 @@ hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg
 
 template <typename T, int VEC, bool UA_OK = false>
 hipError_t launch_softmax_v(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    if (a.k_lengths) return launch_softmax_m<T, VEC, kMaskLengths, UA_OK>(p, a, lc, s);
+    if (a.k_lengths || a.causal) return launch_softmax_m<T, VEC, kMaskLengths, UA_OK>(p, a, lc, s);
     return a.mask ? launch_softmax_m<T, VEC, kMaskAdditive, UA_OK>(p, a, lc, s)
                   : launch_softmax_m<T, VEC, kMaskNone, UA_OK>(p, a, lc, s);
 }

@@ -240,3 +240,83 @@ def test_packed_error_paths():
     assert f(fake, fake + 2, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert f(fake, fake, fake + 4, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert f(fake, fake, fake, 1, 1, 4, 4, 1.0, 9, None) == tb.TURBO_ERR_DTYPE
+
+
+# ------------------------------------------------------------------ causal variant
+
+def _run_causal(scores, q_len, k_len, scale):
+    s = gu.dev(scores)
+    ql = None if q_len is None else torch.from_numpy(np.asarray(q_len, dtype=np.int32)).cuda()
+    kl = None if k_len is None else torch.from_numpy(np.asarray(k_len, dtype=np.int32)).cuda()
+    tb.turbo_masked_softmax_causal(s, ql, kl, scale)
+    torch.cuda.synchronize()
+    return s
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+@pytest.mark.parametrize("path", [-1, tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM])
+def test_causal_softmax_shapes(dtype, path):
+    """Keys above the diagonal are poisoned with NaN: they must be neither read into a result nor left in place."""
+    rng = np.random.Generator(np.random.Philox(41))
+    for B, H, Sq, Sk in [(1, 1, 1, 1), (2, 3, 7, 7), (2, 2, 16, 16), (3, 2, 33, 33), (2, 2, 64, 64), (2, 1, 100, 100), (2, 2, 128, 128),
+                         (1, 2, 257, 257), (1, 1, 512, 512), (1, 1, 1000, 1000), (2, 1, 5, 133), (1, 2, 60, 493), (1, 1, 3, 4100),
+                         (2, 1, 9, 4), (1, 1, 2100, 2100)]:
+        scores = (rng.standard_normal((B, H, Sq, Sk), dtype=np.float32) * 3).astype(dtype)
+        q_idx, k_idx = np.arange(Sq)[:, None], np.arange(Sk)[None, :]
+        hidden = k_idx > q_idx + (Sk - Sq)
+        poisoned = scores.copy()
+        poisoned[:, :, hidden] = np.nan
+        for use_lengths in (False, True):
+            k_len = q_len = None
+            if use_lengths:
+                k_len = rng.integers(0, Sk + 1, size=B)
+                q_len = rng.integers(0, Sq + 1, size=B)
+                k_len[0], q_len[0] = Sk, Sq
+            with gu.overrides(path=path):
+                got = _np(_run_causal(poisoned, q_len, k_len, 0.125))
+            want = orc.masked_softmax_causal(scores, q_len, k_len, 0.125)
+            # rows the call leaves untouched keep their (poisoned) input; compare them bit for bit, the rest by value
+            touched = np.ones((B, Sq), dtype=bool)
+            visible = np.minimum(np.arange(Sq)[None, :] + (Sk - Sq) + 1, Sk if k_len is None else np.asarray(k_len)[:, None])
+            touched &= np.broadcast_to(visible > 0, (B, Sq))
+            if q_len is not None:
+                touched &= np.arange(Sq)[None, :] < np.asarray(q_len)[:, None]
+            what = f"causal softmax {B,H,Sq,Sk} path={path} lengths={use_lengths}"
+            for b in range(B):
+                live = touched[b]
+                if live.any():
+                    assert_parity(got[b][:, live], want[b][:, live], dtype, what)
+                if (~live).any():
+                    np.testing.assert_array_equal(got[b][:, ~live], poisoned[b][:, ~live])
+
+
+def test_causal_softmax_on_config_4_matches_the_additive_mask_kernel():
+    """GPT-2-medium scores [64,16,512,512] fp16: sampled rows against the oracle, and every element against what the
+    additive 0 / -10000 mask kernel produces (the same exact zeros above the diagonal, fp16-close values below)."""
+    spec = wl.config_spec(4)
+    case = wl.softmax_case(spec)
+    masked = gu.run_softmax(case)
+    causal = _run_causal(case.scores, None, None, case.scale)
+    B, H, Sq, Sk = case.shape
+    rows = gu.sample_rows(B * H * Sq, 400, seed=44)
+    got = _np(causal.view(-1, Sk)[torch.from_numpy(rows).cuda()])
+    flat = case.scores.reshape(-1, Sk)[rows]
+    for i, r in enumerate(rows[:200]):
+        q = int(r % Sq)
+        w = orc.masked_softmax(flat[i, :q + 1].reshape(1, 1, 1, q + 1), None, 0, 0, case.scale).reshape(-1)
+        assert_parity(got[i, :q + 1], w, F16, f"causal config 4 row {r}")
+        assert (got[i, q + 1:] == 0).all()
+    diff = (causal.float() - masked.float()).abs().max().item()
+    assert diff <= 2 ** -10, diff  # both round the same fp32 value to fp16, up to one ulp of values <= 1
+    dead = torch.triu(torch.ones(Sq, Sk, dtype=torch.bool, device="cuda"), 1)
+    assert (causal[:, :, dead] == 0).all()
+
+
+def test_causal_error_paths():
+    L = tb.lib()
+    fake = 0x10000
+    # every call below must be rejected by the host-side validation: the pointers are not real
+    assert L.turbo_masked_softmax_causal(None, None, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
+    assert L.turbo_masked_softmax_causal(fake, None, None, 1, 1, 0, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
+    assert L.turbo_masked_softmax_causal(fake, fake + 2, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
+    assert L.turbo_masked_softmax_causal(fake, None, None, 1, 1, 4, 4, 1.0, 3, None) == tb.TURBO_ERR_DTYPE
