@@ -151,7 +151,8 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         }
         // Prefer a lane group that tiles the row exactly (no masked lanes, constant merge weights),
         // e.g. 96 vectors = 32 lanes x 3 rather than 64 lanes x 2 with a quarter of them idle.
-        if (!p.under_aligned && (long long)g * nv * vec != row_len) {
+        // (those shapes exist only in the mode without bounds checks, which per-row key counts rule out)
+        if (!p.under_aligned && !ovr.no_full && (long long)g * nv * vec != row_len) {
             for (int gg = 64; gg >= 4; gg >>= 1) {
                 if (nvec % gg != 0) continue;
                 int q = (int)(nvec / gg);

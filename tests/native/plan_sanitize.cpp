@@ -26,6 +26,8 @@ static int check(int row_len, int es, long long align, long long rows, const OpL
     const long long nvec = ((long long)row_len + p.vec - 1) / p.vec;
     if (p.path == kPathWave) {
         if ((long long)p.lanes * p.nv < nvec || round_up_nv(p.nv) != p.nv || !wave_shape_supported(p.lanes, p.nv)) return bad("wave shape");
+        // lane groups narrower than a wavefront hold several vectors per lane only in the mode without bounds checks
+        if (p.lanes < 64 && p.nv > 1 && !p.full) return bad("narrow lane group with several vectors outside the exact-tiling mode");
         if (p.nv * p.vec > lim.wave_max_epl) return bad("wave registers");
     } else if (p.path == kPathBlock) {
         if (64ll * p.waves * p.nv < nvec || round_up_nv(p.nv) != p.nv || p.waves < 2 || p.waves > kBlockMaxWaves) return bad("block shape");

@@ -33,7 +33,10 @@ def _run_softmax(scores, q_len, k_len, scale):
 def test_varlen_softmax_shapes(dtype, path):
     rng = np.random.Generator(np.random.Philox(21))
     for B, H, S in [(1, 1, 1), (3, 2, 7), (4, 3, 16), (5, 2, 33), (6, 2, 64), (4, 2, 100), (3, 2, 128), (4, 1, 257), (2, 1, 493),
-                    (2, 1, 1000), (1, 1, 2048), (2, 1, 4100)]:
+                    (2, 1, 1000), (1, 1, 2048), (2, 1, 4100),
+                    # row lengths whose vectors tile 32 or 16 lanes exactly (96, 160, 48 vectors): without per-row key
+                    # counts they get a kernel shape that exists only without bounds checks
+                    (2, 1, 384), (1, 1, 640), (2, 1, 192), (1, 1, 768), (1, 1, 1280)]:
         scores = (rng.standard_normal((B, H, S, S), dtype=np.float32) * 3).astype(dtype)
         lens = rng.integers(0, S + 1, size=B)
         lens[0] = S                       # one request fills the batch, as the padded layout implies
@@ -260,7 +263,7 @@ def test_causal_softmax_shapes(dtype, path):
     rng = np.random.Generator(np.random.Philox(41))
     for B, H, Sq, Sk in [(1, 1, 1, 1), (2, 3, 7, 7), (2, 2, 16, 16), (3, 2, 33, 33), (2, 2, 64, 64), (2, 1, 100, 100), (2, 2, 128, 128),
                          (1, 2, 257, 257), (1, 1, 512, 512), (1, 1, 1000, 1000), (2, 1, 5, 133), (1, 2, 60, 493), (1, 1, 3, 4100),
-                         (2, 1, 9, 4), (1, 1, 2100, 2100)]:
+                         (2, 1, 9, 4), (1, 1, 2100, 2100), (1, 1, 384, 384), (1, 1, 3, 640), (1, 1, 5, 768)]:
         scores = (rng.standard_normal((B, H, Sq, Sk), dtype=np.float32) * 3).astype(dtype)
         q_idx, k_idx = np.arange(Sq)[:, None], np.arange(Sk)[None, :]
         hidden = k_idx > q_idx + (Sk - Sq)
