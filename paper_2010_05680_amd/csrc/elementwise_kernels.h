@@ -105,9 +105,8 @@ __global__ __launch_bounds__(kElemThreads) void add_bias_gelu_kernel(GeluArgs a)
         } else if constexpr (WRAP) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                int c = col + j;
-                c = c >= a.hidden ? c - a.hidden : c;
-                b[j] = (float)bias[c];
+                const unsigned c = (unsigned)(col + j);  // may wrap more than once when hidden < VEC
+                b[j] = (float)bias[c - fastdiv(c, a.div_hidden) * (unsigned)a.hidden];
             }
         } else {
             Pack<T, VEC> pb = load_pack<T, VEC, UA>(bias + col);

@@ -133,3 +133,50 @@ def test_every_layernorm_plan(dtype):
                     print(f"layernorm {np.dtype(dtype).name}: {ran} launches", flush=True)
     print(f"layernorm {np.dtype(dtype).name}: {len(plans)} plans, {ran} launches")
     assert len(plans) > 120
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_every_elementwise_kernel_variant(dtype):
+    """bias+GELU: both forms x (hidden a multiple of the vector or not) x (16-byte aligned or not) x (wide or
+    one-element accesses); head permutations: split / merge x bias x vector widths 16..2 bytes x the grouped and
+    the flat kernel."""
+    rng = np.random.Generator(np.random.Philox(53))
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    es = np.dtype(dtype).itemsize
+    rand = lambda shape, std=1.0: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(dtype)
+    ran = 0
+    for hidden in (64, 37, 1, 130):
+        for aligned in (True, False):
+            for cap in (-1, es):
+                for approximate in (False, True):
+                    for use_bias in (True, False):
+                        x, b = rand((23, hidden), 1.5), rand((hidden,), 0.5)
+                        out = torch.full((23 * hidden + 1,), float("nan"), dtype=tdt, device="cuda")
+                        ov = out[(0 if aligned else 1):][:23 * hidden].view(23, hidden)
+                        with gu.overrides(max_vec_bytes=cap):
+                            tb.turbo_add_bias_gelu(_device_view(x, aligned), _device_view(b, aligned) if use_bias else None,
+                                                   approximate, ov)
+                        torch.cuda.synchronize()
+                        assert_parity(ov.cpu().numpy(), orc.add_bias_gelu(x, b if use_bias else None, approximate), dtype,
+                                      f"gelu hidden={hidden} aligned={aligned} cap={cap} approximate={approximate} bias={use_bias}")
+                        ran += 1
+    for D in (64, 36, 6, 5):            # 16-, 8-, 4- and 2-byte vectors for binary16; 16, 16, 8, 4 for binary32
+        for S, Hh in ((8, 4), (7, 3)):  # multiples of four take the grouped kernel, others the flat one
+            for aligned in (True, False):
+                for flat in (False, True):
+                    x5, bias = rand((2, S, 3, Hh, D)), rand((3, Hh, D), 0.3)
+                    y4 = rand((2, Hh, S, D))
+                    with gu.overrides(path=2 if flat else -1):
+                        for use_bias in (True, False):
+                            o5 = torch.full((3, 2, Hh, S, D), float("nan"), dtype=tdt, device="cuda")
+                            tb.turbo_add_bias_split_heads(_device_view(x5, aligned), gu.dev(bias) if use_bias else None, o5)
+                            torch.cuda.synchronize()
+                            assert_parity(o5.cpu().numpy(), orc.add_bias_split_heads(x5, bias if use_bias else None), dtype,
+                                          f"split heads D={D} S={S} H={Hh} aligned={aligned} flat={flat} bias={use_bias}")
+                            ran += 1
+                        o4 = torch.full((2, S, Hh, D), float("nan"), dtype=tdt, device="cuda")
+                        tb.turbo_merge_heads(_device_view(y4, aligned), o4)
+                        torch.cuda.synchronize()
+                        np.testing.assert_array_equal(o4.cpu().numpy().astype(np.float64), orc.merge_heads(y4))
+                        ran += 1
+    print(f"element-wise {np.dtype(dtype).name}: {ran} launches")

@@ -175,7 +175,7 @@ def _run_packed(blocks_flat, lengths, H, scale, dtype, max_len=None, lead=0, tai
 def test_packed_softmax_shapes(dtype):
     rng = np.random.Generator(np.random.Philox(31))
     cases = [([1], 1), ([5], 2), ([3, 0, 1, 2], 3), ([8, 63, 64, 65], 2), ([100, 7, 257, 31, 4], 3), ([493, 5, 128, 500, 17], 12),
-             ([1000, 3], 1), ([2049, 40], 1), ([4096, 9, 4095], 1),
+             ([1000, 3], 1), ([1500, 2], 1), ([2049, 40], 1), ([3000, 77], 1), ([4096, 9, 4095], 1),
              ([3, 1, 4, 1, 5, 9, 2, 6, 0] * 7, 2), ([3, 1, 4, 1, 5, 9, 2, 6] * 9, 2)]  # 63 and 72 requests: both table look-ups
     if dtype == F16:
         cases.append(([8192, 11, 5000], 1))
