@@ -16,7 +16,9 @@ hipError_t gelu_tv(const GeluArgs& a, bool ua, hipStream_t s) {
     const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
 #define TURBO_GELU(APPROX, WRAP, UA) \
     hipLaunchKernelGGL((add_bias_gelu_kernel<T, VEC, APPROX, WRAP, UA>), grid, block, 0, s, a)
-    if (a.approximate) {
+    if constexpr (VEC == 1) {  // one element per access: no vector can straddle a row end or be misaligned
+        if (a.approximate) TURBO_GELU(true, false, false); else TURBO_GELU(false, false, false);
+    } else if (a.approximate) {
         if (wrap) { if (ua) TURBO_GELU(true, true, true); else TURBO_GELU(true, true, false); }
         else      { if (ua) TURBO_GELU(true, false, true); else TURBO_GELU(true, false, false); }
     } else {
@@ -44,10 +46,8 @@ hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
     }
     const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
     if (a.bias) {
-        if (a.out_order)
-            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, true>), grid, block, 0, s, a);
-        else
-            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, false>), grid, block, 0, s, a);
+        if (a.out_order) return hipErrorInvalidValue;  // only the split (input order) takes a bias
+        hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, false>), grid, block, 0, s, a);
     } else {
         if (a.out_order)
             hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, true>), grid, block, 0, s, a);

@@ -468,6 +468,13 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
     return hipGetLastError();
 }
 
+// The shapes the planner can ask for: within the register budget; and with vectors of one or two elements its
+// last pass (smallest workgroup that fits) never lands on 5, 6 or 8 vectors per lane.
+template <int VEC, int NV>
+constexpr bool softmax_block_shape_compiled() {
+    return (NV * VEC <= kSoftmaxLimits.block_max_epl || NV == 1) && (VEC > 2 || (NV != 5 && NV != 6 && NV != 8));
+}
+
 template <typename T, int VEC, int NV, int MK, int MODE>
 hipError_t launch_softmax_block(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     hipLaunchKernelGGL((softmax_block_kernel<T, VEC, NV, MK, MODE>),
@@ -509,15 +516,15 @@ hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCf
     }
     if (p.path == kPathBlock) {
         switch (p.nv) {
-            case 1: if constexpr (1 * VEC <= kSoftmaxLimits.block_max_epl || 1 == 1) return launch_softmax_block<T, VEC, 1, MK, MODE>(p, a, lc, s); else break;
-            case 2: if constexpr (2 * VEC <= kSoftmaxLimits.block_max_epl || 2 == 1) return launch_softmax_block<T, VEC, 2, MK, MODE>(p, a, lc, s); else break;
-            case 3: if constexpr (3 * VEC <= kSoftmaxLimits.block_max_epl || 3 == 1) return launch_softmax_block<T, VEC, 3, MK, MODE>(p, a, lc, s); else break;
-            case 4: if constexpr (4 * VEC <= kSoftmaxLimits.block_max_epl || 4 == 1) return launch_softmax_block<T, VEC, 4, MK, MODE>(p, a, lc, s); else break;
-            case 5: if constexpr (5 * VEC <= kSoftmaxLimits.block_max_epl) return launch_softmax_block<T, VEC, 5, MK, MODE>(p, a, lc, s); else break;
-            case 6: if constexpr (6 * VEC <= kSoftmaxLimits.block_max_epl || 6 == 1) return launch_softmax_block<T, VEC, 6, MK, MODE>(p, a, lc, s); else break;
-            case 8: if constexpr (8 * VEC <= kSoftmaxLimits.block_max_epl || 8 == 1) return launch_softmax_block<T, VEC, 8, MK, MODE>(p, a, lc, s); else break;
-            case 12: if constexpr (12 * VEC <= kSoftmaxLimits.block_max_epl || 12 == 1) return launch_softmax_block<T, VEC, 12, MK, MODE>(p, a, lc, s); else break;
-            case 16: if constexpr (16 * VEC <= kSoftmaxLimits.block_max_epl || 16 == 1) return launch_softmax_block<T, VEC, 16, MK, MODE>(p, a, lc, s); else break;
+            case 1: if constexpr (softmax_block_shape_compiled<VEC, 1>()) return launch_softmax_block<T, VEC, 1, MK, MODE>(p, a, lc, s); else break;
+            case 2: if constexpr (softmax_block_shape_compiled<VEC, 2>()) return launch_softmax_block<T, VEC, 2, MK, MODE>(p, a, lc, s); else break;
+            case 3: if constexpr (softmax_block_shape_compiled<VEC, 3>()) return launch_softmax_block<T, VEC, 3, MK, MODE>(p, a, lc, s); else break;
+            case 4: if constexpr (softmax_block_shape_compiled<VEC, 4>()) return launch_softmax_block<T, VEC, 4, MK, MODE>(p, a, lc, s); else break;
+            case 5: if constexpr (softmax_block_shape_compiled<VEC, 5>()) return launch_softmax_block<T, VEC, 5, MK, MODE>(p, a, lc, s); else break;
+            case 6: if constexpr (softmax_block_shape_compiled<VEC, 6>()) return launch_softmax_block<T, VEC, 6, MK, MODE>(p, a, lc, s); else break;
+            case 8: if constexpr (softmax_block_shape_compiled<VEC, 8>()) return launch_softmax_block<T, VEC, 8, MK, MODE>(p, a, lc, s); else break;
+            case 12: if constexpr (softmax_block_shape_compiled<VEC, 12>()) return launch_softmax_block<T, VEC, 12, MK, MODE>(p, a, lc, s); else break;
+            case 16: if constexpr (softmax_block_shape_compiled<VEC, 16>()) return launch_softmax_block<T, VEC, 16, MK, MODE>(p, a, lc, s); else break;
         }
         return hipErrorInvalidValue;
     }

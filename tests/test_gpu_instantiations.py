@@ -21,10 +21,14 @@ F32, F16 = np.float32, np.float16
 
 B, H, SQ = 4, 1, 10           # 40 rows: a ragged tile for the lane-group kernels, several rows for the others
 ROWS = B * H * SQ
-LENGTHS = list(range(1, 2200)) + list(range(2200, 70001, 37)) + [4096, 8192, 12288, 16384, 24576, 32768, 49152, 65536]
+_NV = (1, 2, 3, 4, 5, 6, 8, 12, 16)
+# every row length below 2200, a coarse scan above, and the lengths that lane groups or workgroups tile exactly
+LENGTHS = sorted(set(list(range(1, 2200)) + list(range(2200, 70001, 37)) +
+                     [lanes * nv * vec for lanes in (4, 8, 16, 32, 64, 128, 256, 512, 1024) for nv in _NV for vec in (1, 2, 4, 8)
+                      if lanes * nv * vec <= 70000]))
 
 
-def _distinct_plans(op, code):
+def _distinct_plans(op, code, shortest=1):
     """{plan text: (row length, aligned, vector cap, forced family)} over the scan; the first length found is kept."""
     plans = {}
     try:
@@ -34,6 +38,8 @@ def _distinct_plans(op, code):
                 tb.turbo_set_override(tb.TURBO_OVR_PATH, path)
                 for aligned in (True, False):
                     for L in LENGTHS:
+                        if L < shortest:
+                            continue
                         text = tb.turbo_describe_plan(op, ROWS, L, code, aligned)
                         plans.setdefault(text, (L, aligned, cap, path))
     finally:
@@ -95,13 +101,11 @@ def test_every_softmax_plan(dtype):
 @pytest.mark.parametrize("dtype", [F32, F16])
 def test_every_layernorm_plan(dtype):
     code = tb.TURBO_F32 if dtype == F32 else tb.TURBO_F16
-    plans = _distinct_plans(1, code)
+    plans = _distinct_plans(1, code, shortest=2)  # a single column has zero variance: eps-dominated, its own test
     rng = np.random.Generator(np.random.Philox(52))
     tdt = torch.float32 if dtype == F32 else torch.float16
     ran = 0
     for text, (L, aligned, cap, path) in plans.items():
-        if L == 1:
-            continue  # a single column has zero variance: eps-dominated, covered by its own test
         normal = lambda shape, std, mean=0.0: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std) + np.float32(mean)).astype(dtype)
         x, res = normal((ROWS, L), 1.0), normal((ROWS, L), 1.0)
         # rows of two or three columns are ill-conditioned when their values nearly coincide (the result then depends on
