@@ -90,20 +90,25 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
         rp[r] = reinterpret_cast<T*>(a.scores) + base + (long long)(row - a.H * first) * n;
     }
 
+    // len[r] is the same in every lane, so "this vector slot lies wholly beyond the row" is a scalar branch: short
+    // rows skip the slots they do not use instead of issuing their (empty) loads.
     float z[R][NV][VEC];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int c = (v * kWave + lane) * VEC;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) z[r][v][j] = -INFINITY;
+            if (v * kWave * VEC >= len[r]) continue;
             if (c + VEC <= len[r]) {
                 const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + c);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * a.scale;
-            } else {  // the row's last, partial vector (one lane per row), or nothing
+            } else if (c < len[r]) {  // the row's last, partial vector: one lane per row
 #pragma unroll
                 for (int j = 0; j < VEC; ++j)
-                    z[r][v][j] = c + j < len[r] ? (float)__builtin_nontemporal_load(rp[r] + c + j) * a.scale : -INFINITY;
+                    if (c + j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + c + j) * a.scale;
             }
         }
 
@@ -142,12 +147,13 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int c = (v * kWave + lane) * VEC;
+            if (v * kWave * VEC >= len[r]) continue;
             if (c + VEC <= len[r]) {
                 Pack<T, VEC> o;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
                 store_stream<T, VEC, true>(rp[r] + c, o);
-            } else {
+            } else if (c < len[r]) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j)
                     if (c + j < len[r]) __builtin_nontemporal_store((T)(z[r][v][j] * inv), rp[r] + c + j);
