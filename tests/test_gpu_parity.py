@@ -271,6 +271,26 @@ def test_layernorm_optional_inputs_and_aliasing():
     assert_parity(_np(r), want, F32, "layernorm out == residual")
 
 
+@pytest.mark.parametrize("path,hidden", [(tb.PATH_WAVE, 1000), (tb.PATH_BLOCK, 4100), (tb.PATH_BLOCK, 12288), (tb.PATH_STREAM, 20000),
+                                         (tb.PATH_STREAM, 771)])
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_layernorm_in_place_in_every_family(path, hidden, dtype):
+    """out == x and out == residual must work whichever kernel family serves the row length: the workgroup-per-row
+    kernels prefetch the next row before they store the current one, the two-sweep kernels read every row twice."""
+    case = wl.random_layernorm_case(75 + hidden, 37, hidden, dtype=dtype, eps=1e-5)
+    want = gu.oracle_layernorm(case)
+    args = (gu.dev(case.bias), gu.dev(case.gamma), gu.dev(case.beta), case.eps)
+    with gu.overrides(path=path):
+        x, r = gu.dev(case.x), gu.dev(case.residual)
+        tb.turbo_add_bias_layernorm_dt(x, r, *args, x)
+        torch.cuda.synchronize()
+        assert_parity(_np(x), want, dtype, f"layernorm out == x, path {path}, hidden {hidden}")
+        x = gu.dev(case.x)
+        tb.turbo_add_bias_layernorm_dt(x, r, *args, r)
+        torch.cuda.synchronize()
+        assert_parity(_np(r), want, dtype, f"layernorm out == residual, path {path}, hidden {hidden}")
+
+
 def test_layernorm_zero_rows_give_beta_and_single_column():
     case = wl.random_layernorm_case(71, 8, 256, eps=1e-5)
     case.x[:] = 0
