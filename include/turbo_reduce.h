@@ -160,9 +160,9 @@ int turbo_add_bias_layernorm_varlen(const void *x, const void *residual, const v
                                     void *out, int dtype, void *stream);
 
 /*
- * Element-wise fused kernels between two GEMMs (Section 4.1.1 names "fused activation functions and fused
- * transpose operations" without printing a formula or a layout; the definitions below are this library's
- * reading).  Same conventions as above; `dtype` is TURBO_F32 or TURBO_F16 with binary32 arithmetic.
+ * Element-wise fused kernels between two GEMMs (Section 4.1.1 names the fused activation and the fused
+ * transposes as the purely element-wise kind of non-GEMM kernel, without printing a formula or a layout; the
+ * definitions below are this library's reading).  Same conventions as above; `dtype` is TURBO_F32 or TURBO_F16 with binary32 arithmetic.
  *
  * turbo_add_bias_gelu:  out[r,j] = gelu(x[r,j] + bias[j]) on [rows, hidden], the feed-forward activation of
  *   the BERT family.  approximate = 0: gelu(t) = t * Phi(t), Phi the standard normal distribution function;
