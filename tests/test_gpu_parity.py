@@ -3,6 +3,8 @@
 Bar: |gpu - oracle| <= max(atol, rtol*|oracle|) with (rtol, atol) = (1e-5, 1e-6) for binary32 and
 (3e-3, 1e-6) for binary16 storage, element by element (conftest.assert_parity).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -405,7 +407,7 @@ def test_hip_graph_capture_and_replay():
             st.synchronize()
 
 
-@pytest.mark.parametrize("chunk", range(4))
+@pytest.mark.parametrize("chunk", range(int(os.environ.get("TURBO_TEST_SWEEP_CHUNKS", "8"))))  # more chunks: a longer hunt
 def test_randomized_shapes_alignments_and_variants(chunk):
     """Seeded sweep over shapes, element types, mask layouts, pointer offsets and forced kernel variants."""
     rng = np.random.default_rng(9000 + chunk)
@@ -445,6 +447,10 @@ def test_randomized_shapes_alignments_and_variants(chunk):
                 continue
             rows = int(rng.integers(1, max(2, min(60, 120000 // L + 1))))
             case = wl.random_layernorm_case(seed, rows, L, dtype=dtype, eps=1e-5)
+            if L < 8:
+                # two or three values that nearly coincide make LayerNorm ill-conditioned (the result then hinges on the
+                # rounding of x + bias + residual, which the oracle does in double); keep such rows well spread
+                case.x[:] = (case.x + np.where(np.arange(L) % 2 == 0, -8.0, 8.0)).astype(dtype)
             n = case.x.size
             obuf = torch.full((n + 16,), float("nan"), dtype=tdt, device="cuda")
             out = obuf[offset:offset + n].view(rows, L)
