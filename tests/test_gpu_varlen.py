@@ -323,3 +323,63 @@ def test_causal_error_paths():
     assert L.turbo_masked_softmax_causal(fake, None, None, 1, 1, 0, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert L.turbo_masked_softmax_causal(fake, fake + 2, None, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert L.turbo_masked_softmax_causal(fake, None, None, 1, 1, 4, 4, 1.0, 3, None) == tb.TURBO_ERR_DTYPE
+
+
+# ------------------------------------------------------------------ seeded random sweep over the length-aware entry points
+
+import os
+
+
+@pytest.mark.parametrize("chunk", range(int(os.environ.get("TURBO_TEST_SWEEP_CHUNKS", "4"))))
+def test_randomized_length_aware_cases(chunk):
+    rng = np.random.default_rng(7000 + chunk)
+    special = [1, 2, 3, 4, 7, 8, 16, 17, 33, 64, 65, 96, 128, 160, 192, 257, 384, 493, 512, 640, 768, 1000, 1280, 2048, 4100]
+    for case_no in range(40):
+        dtype = F32 if rng.random() < 0.5 else F16
+        kind = str(rng.choice(["varlen", "causal", "packed", "layernorm"]))
+        path = int(rng.choice([-1, -1, tb.PATH_WAVE, tb.PATH_BLOCK, tb.PATH_STREAM]))
+        cap = int(rng.choice([-1, -1, -1, 4, 8, 16]))
+        if cap != -1 and cap < np.dtype(dtype).itemsize:
+            cap = -1
+        S = int(rng.choice(special)) if rng.random() < 0.7 else int(rng.integers(1, 1500))
+        B, H = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        what = f"chunk {chunk} case {case_no}: {kind} {np.dtype(dtype).name} B={B} H={H} S={S} path={path} cap={cap}"
+        if kind in ("varlen", "causal"):
+            Sq = S if rng.random() < 0.5 else int(rng.integers(1, max(2, min(S, 24) + 1)))
+            Sq = min(Sq, max(1, 200000 // (S * B * H)))
+            scores = (rng.standard_normal((B, H, Sq, S), dtype=np.float32) * 3).astype(dtype)
+            k_len = rng.integers(0, S + 1, size=B)
+            q_len = rng.integers(0, Sq + 1, size=B)
+            use_q = rng.random() < 0.6
+            with gu.overrides(path=path, max_vec_bytes=cap):
+                if kind == "varlen":
+                    got = _np(_run_softmax(scores, q_len if use_q else None, k_len, 0.125))
+                    want = orc.masked_softmax_varlen(scores, q_len if use_q else None, k_len, 0.125)
+                else:
+                    use_k = rng.random() < 0.5
+                    got = _np(_run_causal(scores, q_len if use_q else None, k_len if use_k else None, 0.125))
+                    want = orc.masked_softmax_causal(scores, q_len if use_q else None, k_len if use_k else None, 0.125)
+            assert_parity(got, want, dtype, what)
+        elif kind == "packed":
+            lengths = [int(v) for v in rng.integers(0, min(S, 600) + 1, size=B)]
+            lengths[0] = max(1, min(S, 600))
+            total = H * sum(n * n for n in lengths)
+            flat = (rng.standard_normal(total, dtype=np.float32) * 3).astype(dtype)
+            lead = int(rng.integers(0, 4))
+            got, buf = _run_packed(flat, lengths, H, 0.125, dtype, max_len=max(lengths) + int(rng.integers(0, 50)) if sum(lengths) > max(lengths) + 50 else None, lead=lead, tail=8)
+            assert_parity(got, orc.masked_softmax_packed(flat, lengths, H, 0.125), dtype, what + f" lengths={lengths}")
+            assert torch.isnan(buf[:lead]).all() and torch.isnan(buf[lead + total:]).all(), what
+        else:
+            hidden = max(S, 8)
+            Sq = max(1, min(int(rng.integers(1, 30)), 100000 // (hidden * B)))
+            tdt = torch.float32 if dtype == F32 else torch.float16
+            normal = lambda shape, std, mean=0.0: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std) + np.float32(mean)).astype(dtype)
+            x, res = normal((B, Sq, hidden), 1.0), normal((B, Sq, hidden), 1.0)
+            bias, gamma, beta = normal((hidden,), 0.1), normal((hidden,), 0.1, 1.0), normal((hidden,), 0.1)
+            lens = rng.integers(0, Sq + 1, size=B).astype(np.int32)
+            out = torch.full((B, Sq, hidden), -7.25, dtype=tdt, device="cuda")
+            with gu.overrides(path=path, max_vec_bytes=cap):
+                tb.turbo_add_bias_layernorm_varlen(gu.dev(x), gu.dev(res), gu.dev(bias), gu.dev(gamma), gu.dev(beta), gu.dev(lens), 1e-5, out)
+            torch.cuda.synchronize()
+            want = orc.add_bias_layernorm_varlen(x, res, bias, gamma, beta, lens, 1e-5, np.full((B, Sq, hidden), -7.25))
+            assert_parity(_np(out), want, dtype, what)
