@@ -181,3 +181,60 @@ def test_stream_probe_copies_and_adds():
     tb.turbo_stream_probe(gu.dev(h), None, od)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(_np(od), h)
+
+
+import os
+
+
+@pytest.mark.parametrize("chunk", range(int(os.environ.get("TURBO_TEST_SWEEP_CHUNKS", "4"))))
+def test_randomized_elementwise_cases(chunk):
+    rng = np.random.default_rng(8000 + chunk)
+    for case_no in range(40):
+        dtype = F32 if rng.random() < 0.5 else F16
+        tdt = torch.float32 if dtype == F32 else torch.float16
+        es = np.dtype(dtype).itemsize
+        cap = int(rng.choice([-1, -1, es, 4, 8]))
+        if cap != -1 and cap < es:
+            cap = -1
+        off = int(rng.integers(0, 4))
+        kind = str(rng.choice(["gelu", "split", "merge"]))
+        what = f"chunk {chunk} case {case_no}: {kind} {np.dtype(dtype).name} cap={cap} off={off}"
+
+        def place(host):  # the array in device memory, `off` elements past an aligned address
+            buf = torch.zeros(host.size + off, dtype=tdt, device="cuda")
+            view = buf[off:].view(host.shape)
+            view.copy_(torch.from_numpy(host))
+            return view
+
+        if kind == "gelu":
+            rows, hidden = int(rng.integers(1, 40)), int(rng.choice([1, 2, 3, 5, 7, 8, 9, 64, 100, 768, 1001, 3072]))
+            x, b = _rand(rng, (rows, hidden), dtype, 1.5), _rand(rng, (hidden,), dtype, 0.5)
+            approximate, use_bias = bool(rng.random() < 0.5), bool(rng.random() < 0.8)
+            obuf = torch.full((x.size + off + 8,), float("nan"), dtype=tdt, device="cuda")
+            ov = obuf[off:off + x.size].view(rows, hidden)
+            with gu.overrides(max_vec_bytes=cap):
+                tb.turbo_add_bias_gelu(place(x), place(b) if use_bias else None, approximate, ov)
+            torch.cuda.synchronize()
+            assert_parity(_np(ov), orc.add_bias_gelu(x, b if use_bias else None, approximate), dtype,
+                          what + f" rows={rows} hidden={hidden} approximate={approximate} bias={use_bias}")
+            assert torch.isnan(obuf[:off]).all() and torch.isnan(obuf[off + x.size:]).all(), what
+        else:
+            B, S, H = int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 9))
+            D = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16, 20, 32, 64, 80]))
+            flat = bool(rng.random() < 0.3)
+            with gu.overrides(max_vec_bytes=cap, path=2 if flat else -1):
+                if kind == "split":
+                    K = int(rng.choice([1, 2, 3]))
+                    x5, bias = _rand(rng, (B, S, K, H, D), dtype), _rand(rng, (K, H, D), dtype, 0.3)
+                    use_bias = bool(rng.random() < 0.7)
+                    out = torch.full((K, B, H, S, D), float("nan"), dtype=tdt, device="cuda")
+                    tb.turbo_add_bias_split_heads(place(x5), place(bias) if use_bias else None, out)
+                    torch.cuda.synchronize()
+                    assert_parity(_np(out), orc.add_bias_split_heads(x5, bias if use_bias else None), dtype,
+                                  what + f" {B,S,K,H,D} bias={use_bias} flat={flat}")
+                else:
+                    y = _rand(rng, (B, H, S, D), dtype)
+                    out = torch.full((B, S, H, D), float("nan"), dtype=tdt, device="cuda")
+                    tb.turbo_merge_heads(place(y), out)
+                    torch.cuda.synchronize()
+                    np.testing.assert_array_equal(_np(out).astype(np.float64), orc.merge_heads(y), err_msg=what + f" {B,H,S,D} flat={flat}")
