@@ -193,7 +193,8 @@ const char *turbo_status_string(int status);
  *   TURBO_OVR_PATH          force a kernel family of the two reductions: 0 wave (a group of lanes per row),
  *                           1 block (a workgroup per row, LDS combine), 2 stream (a workgroup per row, row
  *                           re-read from memory).  A forced family that cannot hold the row falls back to the
- *                           built-in choice.  For the head permutations, 2 selects the flat (ungrouped) kernel.
+ *                           built-in choice.  For the head permutations and bias+GELU, 2 selects the flat kernel
+ *                           (no grouping of rows that share a bias column).
  *   TURBO_OVR_MAX_VEC_BYTES cap the width of one load/store (2..16 bytes); any cap also selects the aligned
  *                           narrow kernels instead of element-aligned 16-byte accesses for odd row lengths
  *   TURBO_OVR_GRID_WAVES    cap on resident workgroups (of 4 wavefronts) per compute unit used to size the grid

@@ -186,6 +186,10 @@ int gelu_impl(const void* x, const void* bias, int rows, int hidden, int approxi
     a.approximate = approximate != 0;
     a.div_hidden = turbo::make_fastdiv((unsigned)hidden);
     a.div_hv = turbo::make_fastdiv((unsigned)(hidden % vec == 0 ? hidden / vec : 1));
+    a.rows = rows;
+    a.hv = 0;
+    a.div_ct = turbo::make_fastdiv(1);
+    a.force_flat = g_ovr.path == 2;  // testing hook, as for the head permutations
     hipError_t err = turbo::launch_add_bias_gelu(a, es, vec, under_aligned, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }

@@ -10,8 +10,41 @@ int grid_for(long long n_vec) {
     return (int)(tiles < 1 ? 1 : tiles);
 }
 
+// Threads per workgroup of the row-slab kernel: the multiple of 64 (at most 256) that wastes the fewest lanes on
+// `hv` vector columns; the larger one on a tie.
+int slab_threads(int hv) {
+    int best = 64;
+    long long best_cost = -1;
+    for (int t = 64; t <= kElemThreads; t += 64) {
+        const long long cost = (long long)((hv + t - 1) / t) * t;
+        if (best_cost < 0 || cost <= best_cost) {
+            best_cost = cost;
+            best = t;
+        }
+    }
+    return best;
+}
+
 template <typename T, int VEC>
-hipError_t gelu_tv(const GeluArgs& a, bool ua, hipStream_t s) {
+hipError_t gelu_tv(const GeluArgs& a0, bool ua, hipStream_t s) {
+    GeluArgs a = a0;
+    if constexpr (VEC > 1) {
+        // rows of at least a wavefront of whole vectors: one bias load per lane serves kElemUnroll rows
+        if (a.hidden % VEC == 0 && a.hidden / VEC >= kWave && a.rows >= kElemUnroll && !a.force_flat) {
+            a.hv = a.hidden / VEC;
+            const int threads = slab_threads(a.hv);
+            const unsigned n_ct = (unsigned)((a.hv + threads - 1) / threads);
+            a.div_ct = make_fastdiv(n_ct);
+            const long long row_tiles = ((long long)a.rows + kElemUnroll - 1) / kElemUnroll;
+            const dim3 grid((unsigned)(row_tiles * n_ct)), block(threads);
+#define TURBO_GELU_ROWS(APPROX, UA) \
+    hipLaunchKernelGGL((add_bias_gelu_rows_kernel<T, VEC, APPROX, UA>), grid, block, 0, s, a)
+            if (a.approximate) { if (ua) TURBO_GELU_ROWS(true, true); else TURBO_GELU_ROWS(true, false); }
+            else               { if (ua) TURBO_GELU_ROWS(false, true); else TURBO_GELU_ROWS(false, false); }
+#undef TURBO_GELU_ROWS
+            return hipGetLastError();
+        }
+    }
     const bool wrap = a.hidden % VEC != 0;
     const dim3 grid(grid_for(a.total / VEC)), block(kElemThreads);
 #define TURBO_GELU(APPROX, WRAP, UA) \

@@ -212,7 +212,7 @@ def test_randomized_elementwise_cases(chunk):
             approximate, use_bias = bool(rng.random() < 0.5), bool(rng.random() < 0.8)
             obuf = torch.full((x.size + off + 8,), float("nan"), dtype=tdt, device="cuda")
             ov = obuf[off:off + x.size].view(rows, hidden)
-            with gu.overrides(max_vec_bytes=cap):
+            with gu.overrides(max_vec_bytes=cap, path=2 if rng.random() < 0.3 else -1):
                 tb.turbo_add_bias_gelu(place(x), place(b) if use_bias else None, approximate, ov)
             torch.cuda.synchronize()
             assert_parity(_np(ov), orc.add_bias_gelu(x, b if use_bias else None, approximate), dtype,

@@ -149,7 +149,7 @@ def test_every_elementwise_kernel_variant(dtype):
     es = np.dtype(dtype).itemsize
     rand = lambda shape, std=1.0: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(dtype)
     ran = 0
-    for hidden in (64, 37, 1, 130):
+    for hidden, flat in ((64, False), (37, False), (1, False), (130, False), (768, False), (768, True), (1000, False), (3072, False)):
         for aligned in (True, False):
             for cap in (-1, es):
                 for approximate in (False, True):
@@ -157,12 +157,12 @@ def test_every_elementwise_kernel_variant(dtype):
                         x, b = rand((23, hidden), 1.5), rand((hidden,), 0.5)
                         out = torch.full((23 * hidden + 1,), float("nan"), dtype=tdt, device="cuda")
                         ov = out[(0 if aligned else 1):][:23 * hidden].view(23, hidden)
-                        with gu.overrides(max_vec_bytes=cap):
+                        with gu.overrides(max_vec_bytes=cap, path=2 if flat else -1):
                             tb.turbo_add_bias_gelu(_device_view(x, aligned), _device_view(b, aligned) if use_bias else None,
                                                    approximate, ov)
                         torch.cuda.synchronize()
                         assert_parity(ov.cpu().numpy(), orc.add_bias_gelu(x, b if use_bias else None, approximate), dtype,
-                                      f"gelu hidden={hidden} aligned={aligned} cap={cap} approximate={approximate} bias={use_bias}")
+                                      f"gelu hidden={hidden} flat={flat} aligned={aligned} cap={cap} approximate={approximate} bias={use_bias}")
                         ran += 1
     for D in (64, 36, 6, 5):            # 16-, 8-, 4- and 2-byte vectors for binary16; 16, 16, 8, 4 for binary32
         for S, Hh in ((8, 4), (7, 3)):  # multiples of four take the grouped kernel, others the flat one
