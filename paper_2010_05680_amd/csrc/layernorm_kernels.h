@@ -331,7 +331,9 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     __shared__ LayerNormLds lds;
-    constexpr bool PRELOAD = NV * VEC <= (FULL ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
+    // 16-byte vectors of 2-byte elements hold their prefetched row in half the registers: they fit like the mode
+    // without bounds checks does
+    constexpr bool PRELOAD = NV * VEC <= ((FULL || (sizeof(T) == 2 && VEC == 8)) ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
