@@ -199,6 +199,8 @@ const char *turbo_status_string(int status);
  *                           narrow kernels instead of element-aligned 16-byte accesses for odd row lengths
  *   TURBO_OVR_GRID_WAVES    cap on resident workgroups (of 4 wavefronts) per compute unit used to size the grid
  *                           of the looping kernels
+ *   TURBO_OVR_BLOCK_WAVES   wavefronts per row (2..16) of the block family, used when the row then fits the
+ *                           registers of that many wavefronts; otherwise the built-in choice stands
  * Returns TURBO_OK, or TURBO_ERR_SHAPE for an unknown key.
  *
  * turbo_describe_plan(op, rows, row_len, dtype, aligned16, buf, buf_len): writes
@@ -220,7 +222,8 @@ const char *turbo_status_string(int status);
  * (TURBO_ERR_SHAPE); out may equal in0 or in1 exactly, other overlap is undefined.
  * Asynchronous on `stream`; allocates nothing.
  */
-enum turbo_override { TURBO_OVR_PATH = 0, TURBO_OVR_MAX_VEC_BYTES = 1, TURBO_OVR_GRID_WAVES = 2, TURBO_OVR_COUNT_ = 3 };
+enum turbo_override { TURBO_OVR_PATH = 0, TURBO_OVR_MAX_VEC_BYTES = 1, TURBO_OVR_GRID_WAVES = 2, TURBO_OVR_BLOCK_WAVES = 3,
+                      TURBO_OVR_COUNT_ = 4 };
 int turbo_set_override(int key, int value);
 int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16, char *buf, int buf_len);
 unsigned turbo_debug_fastdiv(unsigned n, unsigned d);

@@ -343,6 +343,7 @@ int turbo_set_override(int key, int value) {
         case TURBO_OVR_PATH: g_ovr.path = value; return TURBO_OK;
         case TURBO_OVR_MAX_VEC_BYTES: g_ovr.max_vec_bytes = value; return TURBO_OK;
         case TURBO_OVR_GRID_WAVES: g_ovr.grid_waves = value; return TURBO_OK;
+        case TURBO_OVR_BLOCK_WAVES: g_ovr.block_waves = value; return TURBO_OK;
     }
     return TURBO_ERR_SHAPE;
 }

@@ -34,6 +34,10 @@ constexpr int kParamPreloadElems = TURBO_LN_PRELOAD_ELEMS;     // keep bias/gamm
 #endif
 constexpr int kBlockParamPreloadElems = TURBO_LN_BLOCK_PRELOAD_ELEMS;
 constexpr int kBlockParamPreloadFullElems = TURBO_LN_BLOCK_PRELOAD_FULL_ELEMS;
+#ifndef TURBO_LN_BLOCK_PRELOAD_HALF_ELEMS
+#define TURBO_LN_BLOCK_PRELOAD_HALF_ELEMS 24
+#endif
+constexpr int kBlockParamPreloadHalfElems = TURBO_LN_BLOCK_PRELOAD_HALF_ELEMS;  // 16-byte vectors of 2-byte elements
 
 struct LayerNormArgs {
     const void* x;
@@ -115,6 +119,20 @@ __device__ __forceinline__ void load_param(const T* p, int col, float (&dst)[VEC
 #pragma unroll
     for (int j = 0; j < VEC; ++j) dst[j] = (float)raw.v[j];
 }
+// Tells the compiler that a packed register set may have changed (it has not): placed at the top of a loop
+// iteration it keeps the widening conversions of 2-byte parameters inside the loop, i.e. the parameters stay packed
+// in half the registers across iterations instead of being widened once and held in full width.
+template <typename T, int VEC>
+__device__ __forceinline__ void keep_packed(Pack<T, VEC>& p) {
+    if constexpr (sizeof(T) == 2 && VEC % 2 == 0) {
+        struct Words { unsigned w[VEC / 2]; };
+        Words x = __builtin_bit_cast(Words, p);
+#pragma unroll
+        for (int i = 0; i < VEC / 2; ++i) asm volatile("" : "+v"(x.w[i]));
+        p = __builtin_bit_cast(Pack<T, VEC>, x);
+    }
+}
+
 // The bias may be absent: a null pointer reads as zeros (wave-uniform branch).
 template <typename T, int VEC, bool UA = false>
 __device__ __forceinline__ void load_bias(const T* p, int col, float (&dst)[VEC]) {
@@ -333,7 +351,9 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     __shared__ LayerNormLds lds;
     // 16-byte vectors of 2-byte elements hold their prefetched row in half the registers: they fit like the mode
     // without bounds checks does
-    constexpr bool PRELOAD = NV * VEC <= ((FULL || (sizeof(T) == 2 && VEC == 8)) ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
+    constexpr bool PRELOAD = NV * VEC <= ((sizeof(T) == 2 && VEC == 8)
+                                              ? (FULL ? kBlockParamPreloadHalfElems : kBlockParamPreloadFullElems)
+                                              : FULL ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
@@ -368,15 +388,21 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     };
     issue_loads(row);
 
-    float pb[PRELOAD ? NV : 1][VEC], pg[PRELOAD ? NV : 1][VEC], pe[PRELOAD ? NV : 1][VEC];
+    // kept in the storage type (2-byte elements take half the registers) and widened where they are used
+    Pack<T, VEC> pb[PRELOAD ? NV : 1], pg[PRELOAD ? NV : 1], pe[PRELOAD ? NV : 1];
     if constexpr (PRELOAD) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int col = (v * bd + tid) * VEC;
             int colc = FULL ? col : vec_start<VEC, UA>(col, hidden);
-            load_bias<T, VEC, UA>(bias, colc, pb[v]);
-            load_param<T, VEC, UA>(gamma, colc, pg[v]);
-            load_param<T, VEC, UA>(beta, colc, pe[v]);
+            if (bias != nullptr) {
+                pb[v] = load_pack<T, VEC, UA>(bias + colc);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) pb[v].v[j] = (T)0.f;
+            }
+            pg[v] = load_pack<T, VEC, UA>(gamma + colc);
+            pe[v] = load_pack<T, VEC, UA>(beta + colc);
         }
     }
 
@@ -398,6 +424,14 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
     int slot = 0;
     while (true) {
         const long long off = (long long)row * hidden;
+        if constexpr (PRELOAD) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                keep_packed(pb[v]);
+                keep_packed(pg[v]);
+                keep_packed(pe[v]);
+            }
+        }
         float t[NV][VEC];
         float sum = 0.f;
 #pragma unroll
@@ -408,7 +442,7 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
             float b[VEC];
             if constexpr (PRELOAD) {
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) b[j] = pb[v][j];
+                for (int j = 0; j < VEC; ++j) b[j] = (float)pb[v].v[j];
             } else {
                 load_bias<T, VEC, UA>(bias, FULL ? col : vec_start<VEC, UA>(col, hidden), b);
             }
@@ -451,8 +485,8 @@ __global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) 
                 if constexpr (PRELOAD) {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) {
-                        g[j] = pg[v][j];
-                        be[j] = pe[v][j];
+                        g[j] = (float)pg[v].v[j];
+                        be[j] = (float)pe[v].v[j];
                     }
                 } else {
                     load_param<T, VEC, UA>(gamma, colc, g);

@@ -45,6 +45,7 @@ struct OpLimits {
     int block_wide_from_16ths;  // block: 16 wavefronts x 2 vectors replace fewer wavefronts x >= 3 vectors once they
                                 // would use at least this many 16ths of their lanes; 0 = never (measured per operation)
     int block_wide_from_16ths_2byte;  // the same for 2-byte elements
+    int block_exact_first;  // block: 1 = prefer a workgroup of 2..8 wavefronts x 3 or 2 vectors that tiles the row exactly
 };
 #ifndef TURBO_SM_TARGET_ELEMS
 #define TURBO_SM_TARGET_ELEMS 32
@@ -64,8 +65,8 @@ struct OpLimits {
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
 #define TURBO_LN_BLOCK_FROM_BYTES (1 << 30)
 #endif
-constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14};
-constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0};
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14, 0};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0, 1};
 
 struct Plan {
     int path;    // PathKind
@@ -86,6 +87,7 @@ struct Overrides {
     int grid_waves = -1;
     int no_full = 0;    // 1: the call needs per-row bounds checks (per-request lengths), never the exact-tiling mode
     int no_stream = 0;  // 1: the call cannot use the two-sweep family
+    int block_waves = -1;  // 2..16: wavefronts per row in the block family, when the row then fits the register budget
 };
 
 inline int round_up_nv(int nv) {
@@ -170,15 +172,35 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     bool block_ok = false;
     int block_w = 0, block_nv = 0;
     const int block_max_epl = (elem_size == 2 && vec * elem_size >= 16) ? lim.block_max_epl_2byte : lim.block_max_epl;
+    auto block_fits = [&](int nv) {
+        return (nv * vec <= block_max_epl || nv == 1) && (vec * elem_size >= 16 || nv <= lim.block_max_nv_narrow);
+    };
+    // Measured for the LayerNorm: a workgroup that tiles the row exactly with 3 or 2 vectors per lane (any number of
+    // wavefronts up to 8, e.g. 3 x 3 for 576 vectors, 5 x 2 for 640) beats a larger power-of-two workgroup with idle
+    // lanes and bounds checks by up to 12 points.  Workgroups of 5..7 wavefronts that need bounds checks measured
+    // worse than 8, so they are taken for exact tilings only.
+    if (lim.block_exact_first && !p.under_aligned && !ovr.no_full && vec * elem_size >= 16) {
+        for (int nv = 3; nv >= 2 && !block_ok; --nv) {
+            if (nvec % (64 * nv) != 0 || !block_fits(nv)) continue;
+            const long long w = nvec / (64 * nv);
+            // 5..7 wavefronts x 2 vectors gain 1-8 points for 2-byte elements and lose 2 for 4-byte ones
+            if (nv == 2 && w >= 5 && w <= 7 && elem_size != 2) continue;
+            if (w >= 2 && w <= 8) {
+                block_ok = true;
+                block_w = (int)w;
+                block_nv = nv;
+            }
+        }
+    }
     for (int pass = 0; pass < 3 && !block_ok; ++pass) {
         const int max_w = pass == 0 ? 8 : kBlockMaxWaves;
         const int max_nv = pass == 0 ? lim.block_pref_nv : pass == 1 ? 2 * lim.block_pref_nv : kMaxNV;
-        for (int w = 2; w <= max_w; w *= 2) {
+        // 2, 3, 4, 8, 16 wavefronts: three serve rows of 257..384 vectors with a quarter fewer idle lanes than four
+        for (int w = 2; w <= max_w; w = w == 2 ? 3 : w == 3 ? 4 : 2 * w) {
             long long per_lane = (nvec + 64 * w - 1) / (64 * w);
             if (per_lane > kMaxNV) continue;
             int nv = round_up_nv((int)per_lane);
-            const bool fits = (nv * vec <= block_max_epl || nv == 1) &&
-                              (vec * elem_size >= 16 || nv <= lim.block_max_nv_narrow);
+            const bool fits = block_fits(nv);
             if (fits && nv <= max_nv) {
                 block_ok = true;
                 block_w = w;
@@ -187,11 +209,27 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
             }
         }
     }
+    // Rows of 513..704 vectors leave 8 wavefronts x 2 vectors at most 11/16 busy; 4 wavefronts x 3 vectors measured
+    // 4-8 points faster there (softmax), and no slower for the LayerNorm.
+    if (block_ok && block_w == 8 && block_nv == 2 && nvec <= 704 && vec * elem_size >= 16 && block_fits(3)) {
+        block_w = 4;
+        block_nv = 3;
+    }
+    if (ovr.block_waves >= 2 && ovr.block_waves <= kBlockMaxWaves) {
+        const int w = ovr.block_waves;
+        const long long per_lane = (nvec + 64 * w - 1) / (64 * w);
+        const int nv = per_lane <= kMaxNV ? round_up_nv((int)per_lane) : -1;
+        if (nv > 0 && block_fits(nv)) {
+            block_ok = true;
+            block_w = w;
+            block_nv = nv;
+        }
+    }
     // Measured for the softmax: a workgroup of 16 wavefronts with 2 vectors per lane streams better than 8 with
     // 3 or 4, provided enough of its lanes have work (rows of 1536..2048 vectors of binary32, 1792..2048 of binary16;
     // below that the idle lanes cost more than the shape gains).
     const int wide_from = elem_size == 2 ? lim.block_wide_from_16ths_2byte : lim.block_wide_from_16ths;
-    if (block_ok && wide_from > 0 && block_w < kBlockMaxWaves && block_nv >= 3 &&
+    if (block_ok && ovr.block_waves < 2 && wide_from > 0 && block_w < kBlockMaxWaves && block_nv >= 3 &&
         nvec <= 2LL * 64 * kBlockMaxWaves && 16 * nvec >= (long long)wide_from * 2 * 64 * kBlockMaxWaves &&
         2 * vec <= block_max_epl && vec * elem_size >= 16) {
         block_w = kBlockMaxWaves;

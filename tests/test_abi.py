@@ -142,6 +142,22 @@ def test_plan_families_follow_row_length():
     finally:
         tb.turbo_set_override(tb.TURBO_OVR_PATH, -1)
     assert P(0, 30720, 128, tb.TURBO_F32).startswith("wave")
+    # LayerNorm: a workgroup of any size up to 8 wavefronts that tiles the row exactly with 3 or 2 vectors per lane
+    assert P(1, 1000, 4608, tb.TURBO_F16).startswith("block vec=8f waves=3 nv=3")
+    assert P(1, 1000, 5120, tb.TURBO_F16).startswith("block vec=8f waves=5 nv=2")
+    assert P(1, 1000, 6144, tb.TURBO_F16).startswith("block vec=8f waves=4 nv=3")
+    assert P(1, 1000, 7168, tb.TURBO_F16).startswith("block vec=8f waves=7 nv=2")
+    assert P(1, 1000, 2560, tb.TURBO_F32).startswith("block vec=4 waves=4 nv=3")  # not 5 x 2 for 4-byte elements
+    assert P(1, 1000, 2304, tb.TURBO_F32).startswith("block vec=4f waves=3 nv=3")
+    assert P(1, 1000, 2560, tb.TURBO_F16).startswith("block vec=8 waves=3 nv=2")  # three wavefronts, bounds-checked
+    assert P(0, 1000, 4608, tb.TURBO_F16).startswith("block vec=8 waves=4 nv=3")  # 576 vectors: 4 x 3, not 8 x 2
+    assert P(0, 1000, 6144, tb.TURBO_F16).startswith("block vec=8 waves=8 nv=2")
+    tb.turbo_set_override(tb.TURBO_OVR_BLOCK_WAVES, 6)
+    try:
+        assert P(0, 1000, 6144, tb.TURBO_F16).startswith("block vec=8f waves=6 nv=2")
+        assert P(0, 100, 32768, tb.TURBO_F32).startswith("block vec=4f waves=16 nv=8")  # does not fit 6: built-in choice
+    finally:
+        tb.turbo_set_override(tb.TURBO_OVR_BLOCK_WAVES, -1)
     with pytest.raises(tb.TurboError):
         tb.turbo_set_override(99, 0)
 
@@ -159,7 +175,7 @@ def test_planner_invariants_over_many_shapes():
     the plan, so a plan outside these bounds would mean wrong results or reads outside the row."""
     rng = np.random.default_rng(7)
     lens = list(range(1, 300)) + [int(v) for v in rng.integers(300, 70000, size=400)] + \
-        [512, 768, 1024, 1280, 1536, 2048, 2560, 3072, 4096, 5120, 8192, 16384, 32768, 32772, 65536, 100000]
+        [512, 768, 1024, 1280, 1536, 2048, 2304, 2560, 3072, 3584, 4096, 4608, 5120, 6144, 7168, 8192, 10240, 12288, 16384, 32768, 32772, 65536, 100000]
     supported_nv = {1, 2, 3, 4, 5, 6, 8, 12, 16}
     # (operation, most elements per lane: wave family, block family, block family with 16-byte vectors of 2-byte elements)
     for op, wave_max, block_max, block_max_2byte in ((0, 64, 32, 32), (1, 24, 16, 24)):
@@ -185,7 +201,9 @@ def test_planner_invariants_over_many_shapes():
                                 assert lanes * nv * vec == L, what
                         elif fam == "block":
                             w, nv = kv["waves"], kv["nv"]
-                            assert w in (2, 4, 8, 16) and nv in supported_nv, what
+                            assert nv in supported_nv, what
+                            # 5..7 wavefronts only where they tile the row exactly (LayerNorm)
+                            assert w in (2, 3, 4, 8, 16) or (op == 1 and mode == "f" and w in (5, 6, 7) and (nv == 3 or (nv == 2 and es == 2))), what
                             budget = block_max_2byte if (es == 2 and vec == 8) else block_max
                             assert 64 * w * nv >= nvec and (nv * vec <= budget or nv == 1), what
                             if vec * es < 16 and op == 1:

@@ -24,7 +24,7 @@ ROWS = B * H * SQ
 _NV = (1, 2, 3, 4, 5, 6, 8, 12, 16)
 # every row length below 2200, a coarse scan above, and the lengths that lane groups or workgroups tile exactly
 LENGTHS = sorted(set(list(range(1, 2200)) + list(range(2200, 70001, 37)) +
-                     [lanes * nv * vec for lanes in (4, 8, 16, 32, 64, 128, 256, 512, 1024) for nv in _NV for vec in (1, 2, 4, 8)
+                     [lanes * nv * vec for lanes in (4, 8, 16, 32) + tuple(64 * w for w in range(1, 17)) for nv in _NV for vec in (1, 2, 4, 8)
                       if lanes * nv * vec <= 70000]))
 
 
@@ -137,6 +137,52 @@ def test_every_layernorm_plan(dtype):
                     print(f"layernorm {np.dtype(dtype).name}: {ran} launches", flush=True)
     print(f"layernorm {np.dtype(dtype).name}: {len(plans)} plans, {ran} launches")
     assert len(plans) > 120
+
+
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_block_family_with_every_workgroup_size(dtype):
+    """The workgroup-per-row kernels take their number of wavefronts from the launch, 2 to 16; the planner uses only
+    some of them.  Force each one in turn on rows that it tiles exactly, rows with a ragged tail and rows of odd
+    length, with and without per-request lengths."""
+    code = tb.TURBO_F32 if dtype == F32 else tb.TURBO_F16
+    vec = 16 // np.dtype(dtype).itemsize
+    rng = np.random.Generator(np.random.Philox(53))
+    tdt = torch.float32 if dtype == F32 else torch.float16
+    ran = 0
+    for w in range(2, 17):
+        for L in (64 * w * vec, 64 * w * 2 * vec, 64 * w * 2 * vec - 3 * vec, 64 * w * vec + 5, 64 * w * 3 * vec - 1):
+            with gu.overrides(path=tb.PATH_BLOCK, block_waves=w):
+                plans = [tb.turbo_describe_plan(op, ROWS, L, code) for op in (0, 1)]
+            scores = (rng.standard_normal((B, H, SQ, L), dtype=np.float32) * 3).astype(dtype)
+            k_len = rng.integers(0, L + 1, size=B).astype(np.int32)
+            q_len = np.array([SQ, SQ - 3, 0, 1], dtype=np.int32)
+            for kind in ("none", "lengths"):
+                what = f"softmax {plans[0]} | forced waves={w} L={L} mask={kind}"
+                s = gu.dev(scores)
+                with gu.overrides(path=tb.PATH_BLOCK, block_waves=w):
+                    if kind == "none":
+                        tb.turbo_masked_softmax_ex(s, None, 0, 0, 0.125)
+                        want = orc.masked_softmax(scores, None, 0, 0, 0.125)
+                    else:
+                        tb.turbo_masked_softmax_varlen(s, gu.dev(q_len), gu.dev(k_len), 0.125)
+                        want = orc.masked_softmax_varlen(scores, q_len, k_len, 0.125)
+                torch.cuda.synchronize()
+                assert_parity(s.cpu().numpy(), want, dtype, what)
+                ran += 1
+            normal = lambda shape, std, mean=0.0: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std) + np.float32(mean)).astype(dtype)
+            x, res = normal((ROWS, L), 1.0), normal((ROWS, L), 1.0)
+            bias, gamma, beta = normal((L,), 0.1), normal((L,), 0.1, 1.0), normal((L,), 0.1)
+            for residual in (True, False):
+                what = f"layernorm {plans[1]} | forced waves={w} L={L} residual={residual}"
+                out = torch.full((ROWS, L), -7.25, dtype=tdt, device="cuda")
+                with gu.overrides(path=tb.PATH_BLOCK, block_waves=w):
+                    tb.turbo_add_bias_layernorm_dt(gu.dev(x), gu.dev(res) if residual else None, gu.dev(bias), gu.dev(gamma),
+                                                   gu.dev(beta), 1e-5, out)
+                torch.cuda.synchronize()
+                assert_parity(out.cpu().numpy(), orc.add_bias_layernorm(x, res if residual else None, bias, gamma, beta, 1e-5),
+                              dtype, what)
+                ran += 1
+        print(f"workgroup sizes {np.dtype(dtype).name}: waves={w} done, {ran} launches", flush=True)
 
 
 @pytest.mark.parametrize("dtype", [F32, F16])
