@@ -613,8 +613,29 @@ constexpr bool block_shape_compiled() {
 
 template <typename T, int VEC, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>),
-                       dim3(capped_grid(a.n_rows, p.waves, kLayerNormBlockCap, lc)), dim3(64 * p.waves), 0, s, a);
+    // The kernel loops over rows with a fixed assignment of rows to workgroups, so the grid is a whole number of
+    // "rounds" of what the chip holds at once: a partial last round would run with most compute units idle.
+    static int resident[kBlockMaxWaves + 1];  // workgroups of w wavefronts that fit one compute unit; 0 = not asked yet
+    int per_cu = resident[p.waves];
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, layernorm_block_kernel<T, VEC, NV, RES, MODE>, 64 * p.waves, 0) !=
+                hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = 16 / p.waves;
+        }
+        resident[p.waves] = per_cu = n;
+    }
+    int grid;
+    if (lc.waves_per_cu > 0) {
+        grid = capped_grid(a.n_rows, p.waves, kLayerNormBlockCap, lc);
+    } else {
+        // measured: small workgroups stream best with three rounds, workgroups of 5 or more wavefronts with one
+        const int rounds = p.waves <= 4 ? 3 : 1;
+        const long long cap = (long long)lc.num_cus * per_cu * rounds;
+        grid = (int)(a.n_rows < cap ? a.n_rows : cap);
+    }
+    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>), dim3(grid), dim3(64 * p.waves), 0, s, a);
     return hipGetLastError();
 }
 

@@ -54,7 +54,7 @@ struct LaunchCfg {
 // its lane-group family launches one tile of rows per workgroup.
 constexpr int kSoftmaxWaveCap = 0;
 constexpr int kSoftmaxBlockCap = 0;
-constexpr int kLayerNormBlockCap = 32;
+constexpr int kLayerNormBlockCap = 32;  // only with the caller's cap; by default its grid is whole rounds of resident workgroups
 constexpr int kStreamCap = 32;
 
 constexpr int rows_in_flight_c(int nv, int vec, int target) {
