@@ -63,7 +63,7 @@ struct OpLimits {
 #define TURBO_SM_BLOCK_FROM_BYTES 4096
 #endif
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
-#define TURBO_LN_BLOCK_FROM_BYTES (1 << 30)
+#define TURBO_LN_BLOCK_FROM_BYTES 5124  // rows of more than 1280 floats (6 vectors per lane in the wave family): +2-3 points
 #endif
 constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14, 0};
 constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0, 1};
