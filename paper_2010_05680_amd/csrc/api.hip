@@ -322,7 +322,12 @@ int turbo_masked_softmax_packed(void* scores, const int* cu_seqlens, const long 
     a.H = H;
     a.n_rows = H * total_tokens;
     a.scale = scale;
-    const hipError_t err = turbo::launch_softmax_packed(a, es, max_len, reinterpret_cast<hipStream_t>(stream));
+    int num_cus = 0;
+    if (int st = current_num_cus(&num_cus)) return st;
+    // testing hooks: TURBO_OVR_PATH = 0 selects the kernel that gives every row a whole wavefront (the one batches of
+    // 64 or more requests use), TURBO_OVR_GRID_WAVES caps the grid
+    const hipError_t err = turbo::launch_softmax_packed(a, es, max_len, num_cus, g_ovr.grid_waves > 0 ? g_ovr.grid_waves : 0,
+                                                        g_ovr.path == 0, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }
 

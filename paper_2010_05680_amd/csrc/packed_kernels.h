@@ -5,8 +5,9 @@
 // neither bytes nor arithmetic are spent on padding.  Rows of one launch now differ in length, so the compile-time
 // row shapes of the padded kernels do not apply: one wavefront owns one row, holds it in registers (NV vectors per
 // lane, sized for the longest request) and masks what lies beyond the row's own length.  Row starts have element
-// alignment only, so the 16-byte accesses are the element-aligned ones; the last, partial vector of a row is moved
-// element by element by the one lane that owns it.
+// alignment only, so the 16-byte accesses are the element-aligned ones; the lane that owns a row's last, partial
+// vector accesses the vector that ends at the row end instead (overlapping its neighbour's), so a row costs no extra
+// memory instructions; only rows shorter than one vector are moved element by element.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -33,6 +34,13 @@ constexpr int kPackedWaves = 4;  // wavefronts per workgroup
 constexpr int packed_rows_in_flight(int nv, int vec) {
     const int r = TURBO_PACKED_TARGET_ELEMS / (nv * vec);
     return r >= 4 ? 4 : r >= 2 ? 2 : 1;
+}
+
+// First element of the vector that a lane assigned to column c of a row of n >= VEC elements accesses: c itself, or
+// n - VEC for the row's last, partial vector.
+template <int VEC>
+__device__ __forceinline__ int packed_vec_start(int c, int n) {
+    return c + VEC <= n ? c : (n - VEC > 0 ? n - VEC : 0);
 }
 
 template <typename T, int VEC, int NV>
@@ -101,14 +109,18 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
 #pragma unroll
             for (int j = 0; j < VEC; ++j) z[r][v][j] = -INFINITY;
             if (v * kWave * VEC >= len[r]) continue;
-            if (c + VEC <= len[r]) {
-                const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + c);
+            if (len[r] >= VEC) {
+                // the lane that owns the row's last, partial vector reads the vector that ends at the row end instead
+                // (it overlaps the neighbour's by VEC - len % VEC elements, which this lane leaves out of the sum)
+                if (c < len[r]) {
+                    const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, len[r]));
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * a.scale;
-            } else if (c < len[r]) {  // the row's last, partial vector: one lane per row
+                    for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * a.scale;
+                }
+            } else if (c == 0) {  // a row shorter than one vector: element by element, one lane
 #pragma unroll
                 for (int j = 0; j < VEC; ++j)
-                    if (c + j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + c + j) * a.scale;
+                    if (j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * a.scale;
             }
         }
 
@@ -131,11 +143,12 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int c = (v * kWave + lane) * VEC;
+            const int dup = c - packed_vec_start<VEC>(c, len[r]);  // leading elements that the neighbour already counts
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                const float e = c + j < len[r] ? fast_exp2(fmaf(z[r][v][j], kLog2e, shift)) : 0.f;
+                const float e = fast_exp2(fmaf(z[r][v][j], kLog2e, shift));  // 0 where nothing was loaded (-inf)
                 z[r][v][j] = e;
-                l[r] += e;
+                l[r] += j >= dup ? e : 0.f;
             }
         }
     }
@@ -148,21 +161,219 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
         for (int v = 0; v < NV; ++v) {
             const int c = (v * kWave + lane) * VEC;
             if (v * kWave * VEC >= len[r]) continue;
-            if (c + VEC <= len[r]) {
-                Pack<T, VEC> o;
+            if (len[r] >= VEC) {
+                if (c < len[r]) {  // the overlapped elements are written twice, with the same values
+                    Pack<T, VEC> o;
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
-                store_stream<T, VEC, true>(rp[r] + c, o);
-            } else if (c < len[r]) {
+                    for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
+                    store_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, len[r]), o);
+                }
+            } else if (c == 0) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j)
-                    if (c + j < len[r]) __builtin_nontemporal_store((T)(z[r][v][j] * inv), rp[r] + c + j);
+                    if (j < len[r]) __builtin_nontemporal_store((T)(z[r][v][j] * inv), rp[r] + j);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Batches of up to 63 requests: the row shape follows each request's own length.
+//
+// All rows of a request have its length, so a wavefront that works on one request at a time can use the lane-group
+// shape of the padded kernels for exactly that length: a request of 100 floats gets 32 lanes per row and eight rows
+// per wavefront in flight instead of one row on 25 of 64 lanes.  The unit of work is a "task": `rows per wavefront`
+// consecutive rows of one request.  Every wavefront derives the task list itself from the length table (one entry per
+// lane, one prefix sum over the wavefront), so the host, which never sees the lengths, only needs an upper bound on
+// the number of tasks for the grid.
+// ---------------------------------------------------------------------------
+struct PackedShape {
+    int g;   // lanes per row: 8, 16, 32 or 64
+    int nv;  // vectors per lane: 1 unless g == 64, then a power of two
+    int r;   // rows in flight per lane group
+};
+
+template <int VEC>
+__host__ __device__ constexpr PackedShape packed_shape(int n) {
+    const int nvec = (n + VEC - 1) / VEC;
+    PackedShape s{nvec <= 8 ? 8 : nvec <= 16 ? 16 : nvec <= 32 ? 32 : 64, 1, 1};
+    while (kWave * s.nv < nvec) s.nv *= 2;
+    s.r = packed_rows_in_flight(s.nv, VEC);
+    return s;
+}
+// rows of one task; a power of two that does not grow with n, so the longest request bounds the task count
+template <int VEC>
+__host__ __device__ constexpr int packed_task_rows(int n) {
+    const PackedShape s = packed_shape<VEC>(n);
+    return (kWave / s.g) * s.r;
+}
+
+// One task: rows row0 .. row0 + (64/G)*R - 1 of a request whose rows (n elements each) start at `base`.
+template <typename T, int VEC, int G, int NV>
+__device__ __forceinline__ void packed_task(T* base, int n, int row0, int rows_b, float scale, int lane) {
+    constexpr int R = packed_rows_in_flight(NV, VEC);
+    constexpr int GPW = kWave / G;
+    const int grp = lane / G;
+    const int gl = lane & (G - 1);
+
+    int len[R];  // n, or 0 for a row past the request's last one
+    T* rp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = row0 + r * GPW + grp;
+        len[r] = row < rows_b ? n : 0;
+        rp[r] = base + (long long)(row < rows_b ? row : 0) * n;
+    }
+
+    float z[R][NV][VEC];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int c = (v * G + gl) * VEC;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) z[r][v][j] = -INFINITY;
+            if (v * G * VEC >= n) continue;  // same in every lane: a scalar branch
+            if (n >= VEC) {
+                if (c < len[r]) {
+                    const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, n));
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * scale;
+                }
+            } else if (gl == 0) {  // rows shorter than one vector: element by element, one lane per row
+#pragma unroll
+                for (int j = 0; j < VEC; ++j)
+                    if (j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * scale;
+            }
+        }
+
+    float m[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        m[r] = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) m[r] = fmaxf(m[r], z[r][v][j]);
+    }
+    group_allreduce<G, R>(m, MaxOp{});
+
+    float l[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float shift = len[r] > 0 ? -m[r] * kLog2e : 0.f;
+        l[r] = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int c = (v * G + gl) * VEC;
+            const int dup = c - packed_vec_start<VEC>(c, n);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float e = fast_exp2(fmaf(z[r][v][j], kLog2e, shift));
+                z[r][v][j] = e;
+                l[r] += j >= dup ? e : 0.f;
+            }
+        }
+    }
+    group_allreduce<G, R>(l, SumOp{});
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float inv = fast_rcp(l[r]);
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int c = (v * G + gl) * VEC;
+            if (v * G * VEC >= n) continue;
+            if (n >= VEC) {
+                if (c < len[r]) {
+                    Pack<T, VEC> o;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[r][v][j] * inv);
+                    store_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, n), o);
+                }
+            } else if (gl == 0) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j)
+                    if (j < len[r]) __builtin_nontemporal_store((T)(z[r][v][j] * inv), rp[r] + j);
+            }
+        }
+    }
+}
+
+// NVMAX: vectors per lane that the longest request needs (a power of two); longer requests are left untouched.
+template <typename T, int VEC, int NVMAX>
+__global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_groups_kernel(PackedSoftmaxArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave_id = (int)blockIdx.x * kPackedWaves + (int)(threadIdx.x >> 6);
+    const int n_waves = (int)gridDim.x * kPackedWaves;
+
+    // lane b holds request b's length, block offset and task count (B <= 63, so lane B holds the end of the table)
+    int cu_l = 0;
+    long long off_l = 0;
+    if (lane <= a.B) {
+        cu_l = a.cu_seqlens[lane];
+        off_l = a.score_offsets[lane];
+    }
+    int n_l = __shfl_down(cu_l, 1) - cu_l;
+    if (lane >= a.B || n_l < 0 || n_l > kWave * NVMAX * VEC) n_l = 0;
+    const int rows_l = a.H * n_l;
+    const int task_rows_l = packed_task_rows<VEC>(n_l > 0 ? n_l : 1);
+    const int tasks_l = (rows_l + task_rows_l - 1) / task_rows_l;
+    int incl = tasks_l;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    const int total = __shfl(incl, kWave - 1);
+    const int excl = lane < a.B ? incl - tasks_l : 0x7FFFFFFF;
+
+    for (int t = wave_id; t < total; t += n_waves) {
+        // the request of task t: the last lane whose first task is <= t (requests without tasks share their
+        // successor's first task and are passed over)
+        const int b = __builtin_amdgcn_readfirstlane(__popcll(__ballot(excl <= t)) - 1);
+        const int n = __builtin_amdgcn_readfirstlane(__shfl(n_l, b));
+        const int first = __builtin_amdgcn_readfirstlane(__shfl(excl, b));
+        const long long off = __shfl(off_l, b);
+        T* base = reinterpret_cast<T*>(a.scores) + off;
+        const int rows_b = a.H * n;
+        const int row0 = (t - first) * packed_task_rows<VEC>(n);
+        const int nvec = (n + VEC - 1) / VEC;
+        if (nvec <= 8) {
+            packed_task<T, VEC, 8, 1>(base, n, row0, rows_b, a.scale, lane);
+        } else if (nvec <= 16) {
+            packed_task<T, VEC, 16, 1>(base, n, row0, rows_b, a.scale, lane);
+        } else if (nvec <= 32) {
+            packed_task<T, VEC, 32, 1>(base, n, row0, rows_b, a.scale, lane);
+        } else if (nvec <= 64) {
+            packed_task<T, VEC, 64, 1>(base, n, row0, rows_b, a.scale, lane);
+        } else {
+            if constexpr (NVMAX >= 2) {
+                if (nvec <= 128) {
+                    packed_task<T, VEC, 64, 2>(base, n, row0, rows_b, a.scale, lane);
+                } else {
+                    if constexpr (NVMAX >= 4) {
+                        if (nvec <= 256) {
+                            packed_task<T, VEC, 64, 4>(base, n, row0, rows_b, a.scale, lane);
+                        } else {
+                            if constexpr (NVMAX >= 8) {
+                                if (nvec <= 512) {
+                                    packed_task<T, VEC, 64, 8>(base, n, row0, rows_b, a.scale, lane);
+                                } else {
+                                    if constexpr (NVMAX >= 16) packed_task<T, VEC, 64, 16>(base, n, row0, rows_b, a.scale, lane);
+                                }
+                            }
+                        }
+                    }
+                }
             }
         }
     }
 }
 
 // max_len decides the register shape; returns hipErrorInvalidValue when a row of max_len does not fit a wavefront.
-hipError_t launch_softmax_packed(const PackedSoftmaxArgs& a, int elem_size, int max_len, hipStream_t s);
+// num_cus / grid_cap_per_cu (workgroups per compute unit, 0 = none) size the grid of the request-shaped kernel.
+hipError_t launch_softmax_packed(const PackedSoftmaxArgs& a, int elem_size, int max_len, int num_cus, int grid_cap_per_cu,
+                                 bool rows_kernel, hipStream_t s);
 
 }  // namespace turbo

@@ -182,11 +182,15 @@ def test_packed_softmax_shapes(dtype):
     for lengths, H in cases:
         total = H * sum(n * n for n in lengths)
         flat = (rng.standard_normal(total, dtype=np.float32) * 3).astype(dtype)
-        for lead in (0, 3):  # row starts are only element-aligned either way; an odd base pointer on top
-            got, buf = _run_packed(flat, lengths, H, 0.125, dtype, lead=lead, tail=16)
-            want = orc.masked_softmax_packed(flat, lengths, H, 0.125)
-            assert_parity(got, want, dtype, f"packed softmax lengths={lengths} H={H} lead={lead}")
-            assert torch.isnan(buf[:lead]).all() and torch.isnan(buf[lead + total:]).all(), "wrote outside the batch"
+        want = orc.masked_softmax_packed(flat, lengths, H, 0.125)
+        # the request-shaped kernel (up to 63 requests) with its own grid and with so small a grid that every
+        # wavefront loops over several tasks, and the kernel that gives every row a whole wavefront
+        for mode in ({}, {"grid_waves": 1}, {"path": 0}):
+            for lead in (0, 3):  # row starts are only element-aligned either way; an odd base pointer on top
+                with gu.overrides(**mode):
+                    got, buf = _run_packed(flat, lengths, H, 0.125, dtype, lead=lead, tail=16)
+                assert_parity(got, want, dtype, f"packed softmax lengths={lengths} H={H} lead={lead} {mode}")
+                assert torch.isnan(buf[:lead]).all() and torch.isnan(buf[lead + total:]).all(), "wrote outside the batch"
 
 
 def test_packed_softmax_max_len_is_an_upper_bound_and_longer_requests_are_left_alone():
