@@ -407,6 +407,39 @@ def test_hip_graph_capture_and_replay():
             st.synchronize()
 
 
+_FIRST_USE_UNDER_CAPTURE = r"""
+import sys
+import numpy as np, torch
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
+from paper_2010_05680_amd import binding as tb, workloads as wl
+import gpu_util as gu
+case = wl.random_layernorm_case(77, 300, 5120, dtype=np.float16, eps=1e-5)
+x, r, b, g, be = (gu.dev(v) for v in (case.x, case.residual, case.bias, case.gamma, case.beta))
+out = torch.full(case.x.shape, float("nan"), dtype=torch.float16, device="cuda")
+st = torch.cuda.Stream()
+with torch.cuda.stream(st):
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):   # the very first call of this kernel in the process is the captured one
+        tb.turbo_add_bias_layernorm_dt(x, r, b, g, be, case.eps, out, stream=st)
+    for _ in range(2):
+        out.fill_(float("nan")); st.synchronize(); graph.replay(); st.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        want = gu.oracle_layernorm(case)
+        assert np.all(np.abs(got - want) <= np.maximum(1e-6, 3e-3 * np.abs(want))), float(np.abs(got - want).max())
+print("captured first use ok", tb.turbo_describe_plan(1, 300, 5120, tb.TURBO_F16))
+"""
+
+
+def test_first_use_of_a_looping_kernel_inside_graph_capture():
+    """The looping LayerNorm kernel asks the runtime once per kernel for its resident workgroups per compute unit.
+    In a fresh process that first call may come during stream capture: the capture must survive it."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", _FIRST_USE_UNDER_CAPTURE, root], capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0 and "captured first use ok" in res.stdout, res.stdout + res.stderr
+
+
 @pytest.mark.parametrize("chunk", range(int(os.environ.get("TURBO_TEST_SWEEP_CHUNKS", "8"))))  # more chunks: a longer hunt
 def test_randomized_shapes_alignments_and_variants(chunk):
     """Seeded sweep over shapes, element types, mask layouts, pointer offsets and forced kernel variants."""
