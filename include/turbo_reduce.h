@@ -200,7 +200,8 @@ const char *turbo_status_string(int status);
  *   TURBO_OVR_GRID_WAVES    cap on resident workgroups (of 4 wavefronts) per compute unit used to size the grid
  *                           of the looping kernels
  *   TURBO_OVR_BLOCK_WAVES   wavefronts per row (2..16) of the block family, used when the row then fits the
- *                           registers of that many wavefronts; otherwise the built-in choice stands
+ *                           registers of that many wavefronts and is accessed with 16-byte vectors; otherwise the
+ *                           built-in choice stands
  * Returns TURBO_OK, or TURBO_ERR_SHAPE for an unknown key.
  *
  * turbo_describe_plan(op, rows, row_len, dtype, aligned16, buf, buf_len): writes

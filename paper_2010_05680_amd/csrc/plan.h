@@ -215,7 +215,8 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         block_w = 4;
         block_nv = 3;
     }
-    if (ovr.block_waves >= 2 && ovr.block_waves <= kBlockMaxWaves) {
+    // (16-byte vectors only: with narrower ones not every count of vectors per lane is compiled)
+    if (ovr.block_waves >= 2 && ovr.block_waves <= kBlockMaxWaves && vec * elem_size >= 16) {
         const int w = ovr.block_waves;
         const long long per_lane = (nvec + 64 * w - 1) / (64 * w);
         const int nv = per_lane <= kMaxNV ? round_up_nv((int)per_lane) : -1;

@@ -31,6 +31,11 @@ static int check(int row_len, int es, long long align, long long rows, const OpL
         if (p.nv * p.vec > lim.wave_max_epl) return bad("wave registers");
     } else if (p.path == kPathBlock) {
         if (64ll * p.waves * p.nv < nvec || round_up_nv(p.nv) != p.nv || p.waves < 2 || p.waves > kBlockMaxWaves) return bad("block shape");
+        {   // the register budget that decides which shapes are compiled
+            const int budget = (es == 2 && p.vec * es >= 16) ? lim.block_max_epl_2byte : lim.block_max_epl;
+            if (p.nv * p.vec > budget && p.nv != 1) return bad("block registers");
+            if (p.vec * es < 16 && p.nv > lim.block_max_nv_narrow) return bad("narrow vectors per lane");
+        }
         // shapes the softmax launcher leaves out because the planner never asks for them
         if (&lim == &kSoftmaxLimits && p.vec <= 2 && (p.nv == 5 || p.nv == 6 || p.nv == 8)) return bad("softmax block shape that is not compiled");
     } else if (p.path != kPathStream) {
@@ -51,10 +56,12 @@ int main() {
         for (int es : {4, 2})
             for (long long align : {1ll, 2ll, 4ll, 8ll, 16ll})
                 for (int path : {-1, 0, 1, 2})
-                    for (int cap : {-1, 2, 4, 8, 16}) {
+                    for (int cap : {-1, 2, 4, 8, 16})
+                    for (int block_waves : {-1, 2, 3, 5, 7, 8, 11, 16}) {
                         Overrides ovr;
                         ovr.path = path;
                         ovr.max_vec_bytes = cap;
+                        ovr.block_waves = block_waves;
                         for (int no_full : {0, 1}) {
                             ovr.no_full = no_full;
                             for (int len : edge)
@@ -62,7 +69,7 @@ int main() {
                                     if (check(len, es, align, rows, *lim, ovr)) return 1;
                                     ++n;
                                 }
-                            for (int i = 0; i < 200; ++i) {
+                            for (int i = 0; i < 60; ++i) {
                                 const int len = 1 + (int)(rng() % (i % 2 ? 70000u : 3000u));
                                 if (check(len, es, align, 1 + (long long)(rng() % 100000), *lim, ovr)) return 1;
                                 ++n;

@@ -444,9 +444,11 @@ def test_first_use_of_a_looping_kernel_inside_graph_capture():
 def test_randomized_shapes_alignments_and_variants(chunk):
     """Seeded sweep over shapes, element types, mask layouts, pointer offsets and forced kernel variants."""
     rng = np.random.default_rng(9000 + chunk)
+    rng_w = np.random.default_rng(9500 + chunk)  # its own stream: the forced workgroup size of the block family
     special = [1, 2, 3, 4, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 768, 1000,
                1023, 1024, 1025, 1536, 2047, 2048, 2049, 3000, 4095, 4096, 4097, 5000, 8191, 8192]
     for case_no in range(60):
+        block_waves = int(rng_w.choice([-1, -1, -1] + list(range(2, 17))))
         dtype = F32 if rng.random() < 0.5 else F16
         tdt = torch.float32 if dtype == F32 else torch.float16
         L = int(rng.choice(special)) if rng.random() < 0.7 else int(rng.integers(1, 6000))
@@ -457,7 +459,8 @@ def test_randomized_shapes_alignments_and_variants(chunk):
         grid = int(rng.choice([-1, -1, 1, 3]))
         offset = int(rng.integers(0, 8))
         seed = int(rng.integers(1 << 30))
-        what = f"chunk {chunk} case {case_no}: L={L} dtype={np.dtype(dtype).name} path={path} vec={vec_bytes} grid={grid} off={offset}"
+        what = (f"chunk {chunk} case {case_no}: L={L} dtype={np.dtype(dtype).name} path={path} vec={vec_bytes} grid={grid} "
+                f"off={offset} block_waves={block_waves}")
         if rng.random() < 0.5:
             B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
             Sq = int(rng.integers(1, max(2, min(40, 60000 // (L * B * H) + 1))))
@@ -470,7 +473,7 @@ def test_randomized_shapes_alignments_and_variants(chunk):
             view = buf[offset:offset + n].view(case.scores.shape)
             view.copy_(torch.from_numpy(case.scores))
             mask = None if case.mask is None else gu.dev(case.mask)
-            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid):
+            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid, block_waves=block_waves):
                 tb.turbo_masked_softmax_ex(view, mask, case.mask_stride_b, case.mask_stride_q, case.scale)
                 torch.cuda.synchronize()
             assert_parity(_np(view), gu.oracle_softmax(case), dtype, "softmax " + what)
@@ -488,7 +491,7 @@ def test_randomized_shapes_alignments_and_variants(chunk):
             obuf = torch.full((n + 16,), float("nan"), dtype=tdt, device="cuda")
             out = obuf[offset:offset + n].view(rows, L)
             use_res, use_bias = bool(rng.random() < 0.8), bool(rng.random() < 0.8)
-            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid):
+            with gu.overrides(path=path, max_vec_bytes=vec_bytes, grid_waves=grid, block_waves=block_waves):
                 tb.turbo_add_bias_layernorm_dt(gu.dev(case.x), gu.dev(case.residual) if use_res else None,
                                                gu.dev(case.bias) if use_bias else None, gu.dev(case.gamma),
                                                gu.dev(case.beta), case.eps, out)
