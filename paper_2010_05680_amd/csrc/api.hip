@@ -104,6 +104,9 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
     a.n_rows = (int)n_rows;
     a.Sq = Sq;
     a.Sk = Sk;
+    a.B = B;
+    a.H = H;
+    a.compact = 0;
     a.scale = scale;
     a.div_rows_per_batch = turbo::make_fastdiv((unsigned)((long long)H * Sq));
     a.div_sq = turbo::make_fastdiv((unsigned)Sq);

@@ -38,6 +38,8 @@ struct SoftmaxArgs {
     int n_rows;      // B*H*Sq
     int Sq;
     int Sk;
+    int B, H;
+    int compact;     // kMaskLengths, wave family, B <= 63: 1 = workgroups loop over the tiles that hold live rows only
     float scale;
     FastDiv div_rows_per_batch;  // H*Sq
     FastDiv div_sq;              // Sq
@@ -54,6 +56,7 @@ struct LaunchCfg {
 // its lane-group family launches one tile of rows per workgroup.
 constexpr int kSoftmaxWaveCap = 0;
 constexpr int kSoftmaxBlockCap = 0;
+constexpr int kSoftmaxCompactCap = 96;  // length-aware wave family over live tiles only (24 workgroups per compute unit: 16..64 measured alike, 8 was 8 % slower)
 constexpr int kLayerNormBlockCap = 32;  // only with the caller's cap; by default its grid is whole rounds of resident workgroups
 constexpr int kStreamCap = 32;
 
@@ -132,8 +135,50 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
     const int Sk = a.Sk;
     const float scale = a.scale;
 
+    // Compact mode (per-request lengths, up to 63 requests): the padding rows q >= q_len[b] of a zero-padded batch
+    // can be most of the tensor, and tiles made of them alone would still cost a workgroup launch each, or, with a
+    // looping grid, leave the live tiles unevenly spread over the workgroups.  So the tiles are redefined per
+    // (request, head) as chunks of TILE_ROWS live rows, lane b of every wavefront holds request b's tile count, one
+    // prefix sum over the wavefront gives each request's first tile, and the workgroups loop over live tiles only.
+    bool compact = false;
+    int chunks_l = 0, qlen_l = 0, first_l = 0x7FFFFFFF;
+    if constexpr (VARLEN) {
+        compact = a.compact != 0;
+        if (compact) {
+            if (lane < a.B) {
+                qlen_l = a.q_lengths != nullptr ? a.q_lengths[lane] : a.Sq;
+                qlen_l = qlen_l < 0 ? 0 : (qlen_l > a.Sq ? a.Sq : qlen_l);
+                if (a.k_lengths != nullptr && a.k_lengths[lane] <= 0) qlen_l = 0;  // no keys: nothing to do
+            }
+            chunks_l = (qlen_l + TILE_ROWS - 1) / TILE_ROWS;
+            const int tiles_l = a.H * chunks_l;
+            int incl = tiles_l;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int up = __shfl_up(incl, d);
+                if (lane >= d) incl += up;
+            }
+            n_tiles = __shfl(incl, kWave - 1);
+            if (lane < a.B) first_l = incl - tiles_l;
+        }
+    }
+
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
+        int row_base = tile * TILE_ROWS + wave * (R * GPW) + grp;
+        int row_limit = a.n_rows;  // rows from here on are not this tile's
+        if constexpr (VARLEN) {
+            if (compact) {
+                // the request of this tile: the last lane whose first tile is <= tile (requests without live rows
+                // share their successor's first tile and are passed over)
+                const int b = __builtin_amdgcn_readfirstlane(__popcll(__ballot(first_l <= tile)) - 1);
+                const int c = tile - __builtin_amdgcn_readfirstlane(__shfl(first_l, b));
+                const int chunks = __builtin_amdgcn_readfirstlane(__shfl(chunks_l, b));
+                const int h = c / chunks;
+                const int row0 = (b * a.H + h) * a.Sq;
+                row_base = row0 + (c - h * chunks) * TILE_ROWS + wave * (R * GPW) + grp;
+                row_limit = row0 + __builtin_amdgcn_readfirstlane(__shfl(qlen_l, b));
+            }
+        }
 
         Pack<T, VEC> raw[R][NV];
         Pack<T, VEC> mraw[R][NV];
@@ -143,7 +188,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 int row = row_base + r * GPW;
-                klen[r] = row < a.n_rows ? row_key_count(a, row) : 0;
+                klen[r] = row < row_limit ? row_key_count(a, row) : 0;
                 any_row = any_row || klen[r] > 0;
             }
             if (__ballot(any_row) == 0) continue;  // a wavefront whose rows are all padding issues no memory traffic
@@ -463,6 +508,19 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
     constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
     constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
+    if constexpr (MK == kMaskLengths) {
+        if (a.B < kWave && a.q_lengths != nullptr) {
+            // live tiles only: at most this many (every request with all its rows), shared by a grid of looping workgroups
+            SoftmaxArgs c = a;
+            c.compact = 1;
+            const long long bound = (long long)a.B * a.H * ((a.Sq + TILE_ROWS - 1) / TILE_ROWS);
+            n_tiles = (int)(bound < 0x7FFFFFFF ? bound : 0x7FFFFFFF);
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>),
+                               dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxCompactCap, lc)), dim3(64 * kWaveFamilyWaves), 0, s,
+                               c, n_tiles);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
                        dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
     return hipGetLastError();

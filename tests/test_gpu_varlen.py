@@ -53,6 +53,42 @@ def test_varlen_softmax_shapes(dtype, path):
                     np.testing.assert_array_equal(got[b, :, lens[b]:, :], scores[b, :, lens[b]:, :])
 
 
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_varlen_softmax_live_tile_loop_and_large_batches(dtype):
+    """With query lengths and up to 63 requests the lane-group kernels loop over the tiles that hold live rows only
+    (found from the length table inside every wavefront); 64 requests or more keep one tile of consecutive rows per
+    workgroup.  Both sides of that limit, requests without rows or without keys anywhere in the batch, different
+    query and key lengths, a grid so small that every workgroup loops, and padding poisoned with NaN."""
+    rng = np.random.Generator(np.random.Philox(27))
+    for B, H, Sq, Sk in [(63, 1, 9, 40), (64, 1, 9, 40), (70, 2, 5, 24), (7, 3, 50, 50), (5, 2, 33, 128), (9, 1, 20, 300),
+                         (3, 2, 100, 493), (2, 1, 37, 1000)]:
+        scores = (rng.standard_normal((B, H, Sq, Sk), dtype=np.float32) * 3).astype(dtype)
+        q_len = rng.integers(0, Sq + 1, size=B)
+        k_len = rng.integers(0, Sk + 1, size=B)
+        q_len[0], k_len[0] = Sq, Sk
+        q_len[B // 2] = 0                 # a request without rows in the middle of the batch
+        k_len[B - 1] = 0                  # and one without keys at its end
+        if B > 3:
+            q_len[1], k_len[1] = Sq, 1
+        poisoned = scores.copy()
+        for b in range(B):
+            poisoned[b, :, :, k_len[b]:] = np.nan
+            poisoned[b, :, q_len[b]:, :] = np.nan
+        want = orc.masked_softmax_varlen(scores, q_len, k_len, 0.125)
+        for mode in ({}, {"grid_waves": 1}, {"path": tb.PATH_WAVE, "grid_waves": 3}):
+            with gu.overrides(**mode):
+                got = _np(_run_softmax(poisoned, q_len, k_len, 0.125))
+            for b in range(B):
+                what = f"varlen softmax B={B} H={H} Sq={Sq} Sk={Sk} {mode} request {b} (q {q_len[b]}, k {k_len[b]})"
+                if k_len[b] > 0 and q_len[b] > 0:
+                    assert_parity(got[b, :, :q_len[b], :], want[b, :, :q_len[b], :], dtype, what)
+                    assert (got[b, :, :q_len[b], k_len[b]:] == 0).all(), what
+                    assert np.isnan(got[b, :, q_len[b]:, :]).all(), what + ": a padding row was written"
+                else:  # nothing to do for this request: every element keeps its bits
+                    np.testing.assert_array_equal(got[b].view(np.uint16 if dtype == F16 else np.uint32),
+                                                  poisoned[b].view(np.uint16 if dtype == F16 else np.uint32), what)
+
+
 def test_varlen_softmax_rows_too_long_for_registers():
     """Rows beyond 32768 keys go through the two-sweep kernels; padding is poisoned with NaN."""
     rng = np.random.Generator(np.random.Philox(24))
