@@ -35,4 +35,8 @@ def assert_parity(got, oracle, dtype, what=""):
         raise AssertionError(
             f"{what}: {int(bad.sum())} of {bad.size} elements out of tolerance; worst at {i}: "
             f"got {g[i]!r}, oracle {o[i]!r}, |diff| {err[i]:.3e} > {bound[i]:.3e}")
-    return float(err.max()), float((err / np.maximum(np.abs(o), 1e-30)).max())
+    # (largest absolute error, largest relative error among elements whose relative bound is the binding one, largest
+    # error as a fraction of the element's bound)
+    rel_zone = rtol * np.abs(o) >= atol
+    max_rel = float((err[rel_zone] / np.abs(o[rel_zone])).max()) if rel_zone.any() else 0.0
+    return float(err.max()) if err.size else 0.0, max_rel, float((err / bound).max()) if err.size else 0.0

@@ -30,14 +30,16 @@ def _np(t: torch.Tensor) -> np.ndarray:
 def test_softmax_small_configs_full_parity(idx):
     case = wl.softmax_case(wl.config_spec(idx))
     got = _np(gu.run_softmax(case))
-    assert_parity(got, gu.oracle_softmax(case), case.scores.dtype, f"softmax cfg{idx}")
+    err = assert_parity(got, gu.oracle_softmax(case), case.scores.dtype, f"softmax cfg{idx}")
+    print(f"error report: softmax cfg{idx} (all elements): max abs {err[0]:.3e}, max rel {err[1]:.3e}, {100 * err[2]:.0f} % of the bound", flush=True)
 
 
 @pytest.mark.parametrize("idx", [0, 1])
 def test_layernorm_small_configs_full_parity(idx):
     case = wl.layernorm_case(wl.config_spec(idx))
     got = _np(gu.run_layernorm(case))
-    assert_parity(got, gu.oracle_layernorm(case), case.x.dtype, f"layernorm cfg{idx}")
+    err = assert_parity(got, gu.oracle_layernorm(case), case.x.dtype, f"layernorm cfg{idx}")
+    print(f"error report: layernorm cfg{idx} (all elements): max abs {err[0]:.3e}, max rel {err[1]:.3e}, {100 * err[2]:.0f} % of the bound", flush=True)
 
 
 @pytest.mark.parametrize("idx", [2, 3, 4])
@@ -50,7 +52,8 @@ def test_softmax_full_size_configs_sampled_rows_and_invariants(idx):
     n_rows = B * H * Sq
     rows = gu.sample_rows(n_rows, 600, seed=idx)
     got = _np(out.view(n_rows, Sk)[torch.from_numpy(rows).cuda()])
-    assert_parity(got, gu.oracle_softmax_rows(case, rows), case.scores.dtype, f"softmax cfg{idx} sampled rows")
+    err = assert_parity(got, gu.oracle_softmax_rows(case, rows), case.scores.dtype, f"softmax cfg{idx} sampled rows")
+    print(f"error report: softmax cfg{idx} ({len(rows)} sampled rows): max abs {err[0]:.3e}, max rel {err[1]:.3e}, {100 * err[2]:.0f} % of the bound", flush=True)
     # properties that hold at any size, checked on every row
     sums = out.view(n_rows, Sk).float().sum(-1)
     tol = 1e-5 if case.scores.dtype == F32 else 2e-3
@@ -74,7 +77,8 @@ def test_layernorm_full_size_configs_sampled_rows_and_invariants(idx):
     out = gu.run_layernorm(case)
     rows = gu.sample_rows(spec.rows, 600, seed=10 + idx)
     got = _np(out[torch.from_numpy(rows).cuda()])
-    assert_parity(got, gu.oracle_layernorm(case, rows=rows), case.x.dtype, f"layernorm cfg{idx} sampled rows")
+    err = assert_parity(got, gu.oracle_layernorm(case, rows=rows), case.x.dtype, f"layernorm cfg{idx} sampled rows")
+    print(f"error report: layernorm cfg{idx} ({len(rows)} sampled rows): max abs {err[0]:.3e}, max rel {err[1]:.3e}, {100 * err[2]:.0f} % of the bound", flush=True)
     assert torch.isfinite(out).all()
     # undo the affine part on the device: mean 0, variance 1 per row
     g, b = gu.dev(case.gamma).float(), gu.dev(case.beta).float()
