@@ -45,10 +45,16 @@ struct OpLimits {
     int block_wide_from_16ths;  // block: 16 wavefronts x 2 vectors replace fewer wavefronts x >= 3 vectors once they
                                 // would use at least this many 16ths of their lanes; 0 = never (measured per operation)
     int block_wide_from_16ths_2byte;  // the same for 2-byte elements
+    int target_elems_under;  // the same for rows reached with element-aligned accesses (under-aligned mode)
     int block_exact_first;  // block: 1 = prefer a workgroup of 2..8 wavefronts x 3 or 2 vectors that tiles the row exactly
 };
 #ifndef TURBO_SM_TARGET_ELEMS
 #define TURBO_SM_TARGET_ELEMS 32
+#endif
+// Element-aligned 16-byte accesses stream better with fewer of them in flight: measured +2-5 points of HBM peak for
+// every under-aligned softmax shape of the wave family, both element types, with or without an additive mask.
+#ifndef TURBO_SM_TARGET_ELEMS_UNDER
+#define TURBO_SM_TARGET_ELEMS_UNDER 16
 #endif
 #ifndef TURBO_LN_TARGET_ELEMS
 #define TURBO_LN_TARGET_ELEMS 16
@@ -65,8 +71,8 @@ struct OpLimits {
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
 #define TURBO_LN_BLOCK_FROM_BYTES 5124  // rows of more than 1280 floats (6 vectors per lane in the wave family): +2-3 points
 #endif
-constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14, 0};
-constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0, 1};
+constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14, TURBO_SM_TARGET_ELEMS_UNDER, 0};
+constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0, TURBO_LN_TARGET_ELEMS, 1};
 
 struct Plan {
     int path;    // PathKind
@@ -258,7 +264,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     if (path == kPathWave) {
         p.lanes = wave_g;
         p.nv = wave_nv;
-        p.rows = rows_in_flight(p.nv, vec, lim.target_elems);
+        p.rows = rows_in_flight(p.nv, vec, (p.under_aligned && !ovr.no_full) ? lim.target_elems_under : lim.target_elems);
         p.waves = 4;
     } else if (path == kPathBlock) {
         p.waves = block_w;

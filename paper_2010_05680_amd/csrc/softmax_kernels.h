@@ -60,6 +60,15 @@ constexpr int kSoftmaxCompactCap = 96;  // length-aware wave family over live ti
 constexpr int kLayerNormBlockCap = 32;  // only with the caller's cap; by default its grid is whole rounds of resident workgroups
 constexpr int kStreamCap = 32;
 
+// Elements of the rows in flight per lane in the wave family: fewer for element-aligned accesses, except with
+// per-request lengths, where half of a lane's vectors are typically not loaded at all.
+constexpr int softmax_wave_target_elems(int mask_kind, int mode, int row_elems_per_lane) {
+    if (mode != kModeUnder || mask_kind == kMaskLengths) return kSoftmaxLimits.target_elems;
+    // with an additive mask two rows in flight let a per-request key mask be read once for both
+    if (mask_kind == kMaskAdditive && row_elems_per_lane == kSoftmaxLimits.target_elems_under) return 2 * row_elems_per_lane;
+    return kSoftmaxLimits.target_elems_under;
+}
+
 constexpr int rows_in_flight_c(int nv, int vec, int target) {
     int r = target / (nv * vec);
     return r >= 8 ? 8 : r >= 4 ? 4 : r >= 2 ? 2 : 1;
@@ -122,7 +131,7 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     static_assert(!(VARLEN && FULL), "per-row key counts need the bounds checks");
-    constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
+    constexpr int R = rows_in_flight_c(NV, VEC, softmax_wave_target_elems(MK, MODE, NV * VEC));
     constexpr int GPW = kWave / G;  // lane groups per wavefront
     constexpr int kWaves = kWaveFamilyWaves;
     constexpr int TILE_ROWS = R * GPW * kWaves;
@@ -193,6 +202,17 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
             }
             if (__ballot(any_row) == 0) continue;  // a wavefront whose rows are all padding issues no memory traffic
         }
+        // Element-aligned 16-byte loads are the expensive kind, so an under-aligned kernel whose mask does not depend on
+        // the query (stride 0: a per-request key mask) reads the mask once for all rows of the wavefront's share of the
+        // tile, provided they belong to one request (they almost always do: a request has H * Sq rows).
+        bool share_mask = false;
+        if constexpr (MASK && UA && R > 1) {
+            const int first = tile * TILE_ROWS + wave * (R * GPW);
+            int last = first + R * GPW - 1;
+            last = last < a.n_rows ? last : a.n_rows - 1;
+            share_mask = a.mask_stride_q == 0 && first < a.n_rows &&
+                         fastdiv((unsigned)first, a.div_rows_per_batch) == fastdiv((unsigned)last, a.div_rows_per_batch);
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             int row = row_base + r * GPW;
@@ -210,7 +230,12 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
                 } else {
                     raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
                 }
-                if constexpr (MASK) mraw[r][v] = load_pack<T, VEC, UA>(mp + colc);
+                if constexpr (MASK) {
+                    if (UA && R > 1 && r > 0 && share_mask)
+                        mraw[r][v] = mraw[0][v];
+                    else
+                        mraw[r][v] = load_pack<T, VEC, UA>(mp + colc);
+                }
             }
         }
 
@@ -505,7 +530,7 @@ inline int capped_grid(long long work_items, int waves_per_block, int default_ca
 
 template <typename T, int VEC, int G, int NV, int MK, int MODE>
 hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    constexpr int R = rows_in_flight_c(NV, VEC, kSoftmaxLimits.target_elems);
+    constexpr int R = rows_in_flight_c(NV, VEC, softmax_wave_target_elems(MK, MODE, NV * VEC));
     constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
     if constexpr (MK == kMaskLengths) {

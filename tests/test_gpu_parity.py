@@ -259,6 +259,21 @@ def test_unaligned_base_pointers_and_guard_bands(dtype):
         assert torch.isnan(obuf[:31]).all() and torch.isnan(obuf[31 + n:]).all(), "layernorm wrote outside its tensor"
 
 
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_softmax_key_mask_read_once_per_wavefront_for_unaligned_rows(dtype):
+    """Rows that are not 16-byte aligned read a per-request key mask (query stride 0) once for all rows a wavefront
+    holds, when those rows belong to one request.  Requests of 1, 3, 5 and 16 rows make wavefronts straddle requests
+    (no sharing there), larger ones do not; every request has its own mask, so a mask taken from the wrong request
+    shows."""
+    seed = 9700
+    for Sk in (7, 33, 77, 129, 197, 255, 333, 493, 777, 1001):
+        for B, H, Sq in ((9, 1, 1), (7, 1, 3), (5, 1, 5), (4, 2, 8), (3, 2, 33), (2, 3, 64)):
+            seed += 1
+            case = wl.random_softmax_case(seed, B, H, Sq, Sk, dtype=dtype, mask_kind="key")
+            what = f"key mask, unaligned rows: Sk={Sk} B={B} H={H} Sq={Sq}"
+            assert_parity(_np(gu.run_softmax(case)), gu.oracle_softmax(case), dtype, what)
+
+
 def test_layernorm_optional_inputs_and_aliasing():
     case = wl.random_layernorm_case(70, 50, 768, eps=1e-5)
     for residual, bias in [(True, False), (False, True), (False, False)]:
