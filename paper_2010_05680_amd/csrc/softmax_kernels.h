@@ -546,8 +546,15 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
             return hipGetLastError();
         }
     }
+    // Element-aligned 4-byte rows stream best with few wavefronts resident (their accesses straddle cache lines, and the
+    // more of them are in flight the more they thrash): an LDS allocation that the kernel does not use holds a compute
+    // unit at 5 workgroups (20 wavefronts), at 4 for rows of 384 floats and more.  Measured on 77..1001 floats, with and
+    // without an additive mask: +1..4 points of HBM peak (config 2: 128.8 -> 123.2 us); 2-byte elements, which have half the
+    // bytes in flight per wavefront, lose with any such limit.
+    unsigned lds_limit = 0;
+    if constexpr (MODE == kModeUnder && sizeof(T) == 4 && MK != kMaskLengths) lds_limit = a.Sk >= 384 ? 40000 : 32000;
     hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
-                       dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
+                       dim3(64 * kWaveFamilyWaves), lds_limit, s, a, n_tiles);
     return hipGetLastError();
 }
 
