@@ -117,10 +117,11 @@ int turbo_masked_softmax_causal(void *scores, const int *q_lengths, const int *k
  *   for every request b, head h, query q < len_b:   row <- softmax over k < len_b of scale * row.
  *
  * cu_seqlens:    DEVICE int32 [B+1], cumulative lengths: cu_seqlens[0] = 0, cu_seqlens[b+1] - cu_seqlens[b] = len_b >= 0.
- * score_offsets: DEVICE int64 [B+1] (entry B is not read).
+ * score_offsets: DEVICE int64 [B+1] (entry B is not used).
  * total_tokens:  the caller's HOST copy of cu_seqlens[B] (sizes the launch);  max_len: HOST upper bound on len_b
- *                (sizes the registers per row); a request longer than max_len is left untouched.
- * One wavefront holds one row, so max_len is at most 4096 (TURBO_F32) or 8192 (TURBO_F16) (TURBO_ERR_SHAPE beyond).
+ *                (sizes the registers per row); what happens to a request longer than max_len is unspecified (it is
+ *                either computed like the others or left untouched; nothing outside it is touched).
+ * At most one wavefront holds a row, so max_len is at most 4096 (TURBO_F32) or 8192 (TURBO_F16) (TURBO_ERR_SHAPE beyond).
  * The LayerNorm of a packed batch needs no entry point of its own: its tokens are [total_tokens, hidden] rows of
  * turbo_add_bias_layernorm_dt.
  */
