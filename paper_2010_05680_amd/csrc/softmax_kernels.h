@@ -302,29 +302,40 @@ __global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(Sof
 }
 
 // ---------------------------------------------------------------------------
-// Cross-wavefront combine of (max, sum-of-exp) pairs through LDS.
-// Each wavefront publishes the maximum it saw and its sum taken relative to that
-// maximum; one barrier later every lane rebuilds the row's maximum M and sum L
-// and the factor that rescales its own exponentials: exp(m_w - M) / L.
+// Cross-wavefront combine of (reference, sum-of-exp) pairs through LDS.
+// Each wavefront publishes the reference it subtracted in the exponent and its sum
+// taken relative to that reference; one barrier later every lane rebuilds the
+// row's reference M and sum L and the factor that rescales its own exponentials.
+//
+// The reference travels in the base-2 exponent domain: mu_w = fl(m_w * log2 e),
+// rounded ONCE, and that very number is what the wavefront's exponentials
+// exp2(z * log2 e - mu_w) subtracted.  The rescaling exp2(mu_w - M) between two
+// wavefronts then uses the same numbers, so the rounding of m_w * log2 e (an
+// absolute error of |m_w| * 2^-24 in the exponent, 1e-5 relative on the result
+// once |z| reaches a few hundred) cancels between wavefronts exactly as it
+// cancels inside one.  Forming exp2((m_w - M) * log2 e) from the maxima instead
+// would leave every wavefront with its own uncancelled rounding.
 // Two LDS slots alternate between consecutive rows so one barrier per row is enough.
 // ---------------------------------------------------------------------------
 struct SoftmaxLds {
-    float m[2][kBlockMaxWaves];
+    float mu[2][kBlockMaxWaves];
     float l[2][kBlockMaxWaves];
 };
 
+// mu_w: the wavefront's reference (-inf when it saw no element); l_w: its sum of exp2(z log2 e - mu_w).
+// Returns exp2(mu_w - M) / L with M = max_w mu_w and L = sum_w l_w exp2(mu_w - M).
 __device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot, int wave, int lane, int n_waves,
-                                                       float m_w, float l_w) {
+                                                       float mu_w, float l_w) {
     if (lane == 0) {
-        lds.m[slot][wave] = m_w;
+        lds.mu[slot][wave] = mu_w;
         lds.l[slot][wave] = l_w;
     }
     __syncthreads();
     float M = -INFINITY;
-    for (int w = 0; w < n_waves; ++w) M = fmaxf(M, lds.m[slot][w]);
+    for (int w = 0; w < n_waves; ++w) M = fmaxf(M, lds.mu[slot][w]);
     float L = 0.f;
-    for (int w = 0; w < n_waves; ++w) L += lds.l[slot][w] * fast_exp2((lds.m[slot][w] - M) * kLog2e);
-    return fast_exp2((m_w - M) * kLog2e) * fast_rcp(L);  // a wavefront that saw no element has m_w = -inf: factor 0
+    for (int w = 0; w < n_waves; ++w) L += lds.l[slot][w] * fast_exp2(lds.mu[slot][w] - M);
+    return fast_exp2(mu_w - M) * fast_rcp(L);  // a wavefront that saw no element has mu_w = -inf: factor 0
 }
 
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
@@ -388,8 +399,8 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
             }
         }
         group_allreduce<kWave, 1>(m, MaxOp{});
-        const float m_w = m[0];
-        const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
+        const float mu_w = m[0] * kLog2e;  // the wavefront's reference in the exponent domain, rounded once
+        const float shift = (mu_w == -INFINITY) ? 0.f : -mu_w;
 
         float l[1] = {0.f};
 #pragma unroll
@@ -404,7 +415,7 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
         }
         group_allreduce<kWave, 1>(l, SumOp{});
 
-        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
+        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, mu_w, l[0]);
 
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -449,7 +460,8 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
         T* rp = scores + (long long)row * Sk;
         const T* mp = mask_row_ptr<T, MASK>(a, row);
 
-        float m_run = -INFINITY, l_run = 0.f;
+        // running reference in the exponent domain (see softmax_block_combine): mu_run = fl(max * log2 e)
+        float mu_run = -INFINITY, l_run = 0.f;
         for (long long col = (long long)tid * VEC; col < klen; col += step) {
             Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);  // plain: the row is read again below
             Pack<T, VEC> mraw;
@@ -466,26 +478,26 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
                 if constexpr (VARLEN) z[j] = col + j < klen ? z[j] : -INFINITY;  // element 0 of the vector is valid
                 cm = fmaxf(cm, z[j]);
             }
-            if (cm > m_run) {
-                l_run *= fast_exp2((m_run - cm) * kLog2e);  // first chunk: 0 * exp2(-inf) = 0
-                m_run = cm;
+            const float cmu = cm * kLog2e;
+            if (cmu > mu_run) {
+                l_run *= fast_exp2(mu_run - cmu);  // first chunk: 0 * exp2(-inf) = 0
+                mu_run = cmu;
             }
-            const float shift = -m_run * kLog2e;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) l_run += fast_exp2(fmaf(z[j], kLog2e, shift));
+            for (int j = 0; j < VEC; ++j) l_run += fast_exp2(fmaf(z[j], kLog2e, -mu_run));
         }
 
-        float m[1] = {m_run};
+        float m[1] = {mu_run};
         group_allreduce<kWave, 1>(m, MaxOp{});
-        const float m_w = m[0];
+        const float mu_w = m[0];
         float l[1];
-        l[0] = (m_run == -INFINITY) ? 0.f : l_run * fast_exp2((m_run - m_w) * kLog2e);
+        l[0] = (mu_run == -INFINITY) ? 0.f : l_run * fast_exp2(mu_run - mu_w);
         group_allreduce<kWave, 1>(l, SumOp{});
 
-        // factor = exp(m_w - M) / L; the second sweep needs exp(z - M)/L, so fold m_w back in
-        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, m_w, l[0]);
-        // exp2((z - m_w) log2e) * f == exp(z - M)/L; a wavefront with no element stores nothing but zeros
-        const float shift = (m_w == -INFINITY) ? 0.f : -m_w * kLog2e;
+        // factor = exp2(mu_w - M) / L; the second sweep needs exp2(z log2 e - M) / L, so fold mu_w back in
+        const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, mu_w, l[0]);
+        // exp2(z log2 e - mu_w) * f == exp(z - max)/L; a wavefront with no element stores nothing but zeros
+        const float shift = (mu_w == -INFINITY) ? 0.f : -mu_w;
         for (long long col = (long long)tid * VEC; col < Sk; col += step) {
             Pack<T, VEC> o;
             if (VARLEN && col >= klen) {

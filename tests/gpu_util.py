@@ -82,3 +82,57 @@ def sample_rows(n_rows: int, n: int, seed: int, tile: int = 512) -> np.ndarray:
         if 0 <= r < n_rows:
             picks.add(int(r))
     return np.array(sorted(picks), dtype=np.int64)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# every element of a full-size tensor against the oracle, in slabs that keep the float64 temporaries small
+# ---------------------------------------------------------------------------------------------------------------
+
+FULL_CHUNK_ELEMS = 1 << 25  # elements per oracle call: four float64 temporaries of 256 MB each
+
+
+def host_threads() -> int:
+    """Host threads the oracle's row loop may use here (the GPU machine gives a one-GPU job 16)."""
+    import os
+    n = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    return max(1, min(16, n))
+
+
+class ErrorStats:
+    """Running maxima of what conftest.assert_parity returns, plus the element count."""
+
+    def __init__(self):
+        self.max_abs, self.max_rel, self.max_share, self.n = 0.0, 0.0, 0.0, 0
+
+    def add(self, err, n):
+        self.max_abs, self.max_rel = max(self.max_abs, err[0]), max(self.max_rel, err[1])
+        self.max_share = max(self.max_share, err[2])
+        self.n += int(n)
+
+    def line(self, what):
+        return (f"error report: {what} (all elements, {self.n}): max abs {self.max_abs:.3e}, max rel {self.max_rel:.3e}, "
+                f"{100 * self.max_share:.0f} % of the bound")
+
+
+def softmax_slabs(shape, part=0, n_parts=1):
+    """(b, h0, h1) slabs of whole heads of one request, at most FULL_CHUNK_ELEMS elements each; the slabs are dealt
+    round-robin to `n_parts` parts so that every part sees every region of the tensor."""
+    B, H, Sq, Sk = shape
+    hc = max(1, min(H, FULL_CHUNK_ELEMS // (Sq * Sk)))
+    slabs = [(b, h0, min(H, h0 + hc)) for b in range(B) for h0 in range(0, H, hc)]
+    return slabs[part::n_parts]
+
+
+def oracle_softmax_slab(case, b, h0, h1) -> np.ndarray:
+    """The additive-mask oracle on scores[b, h0:h1]: the mask of request b, shared by the heads."""
+    sub = case.scores[b:b + 1, h0:h1]
+    if case.mask is None:
+        return orc.masked_softmax(sub, None, 0, 0, case.scale)[0]
+    m = case.mask.reshape(-1)[b * case.mask_stride_b:]
+    return orc.masked_softmax(sub, m, 0, case.mask_stride_q, case.scale)[0]
+
+
+def row_ranges(n_rows, row_len, part=0, n_parts=1):
+    step = max(1, FULL_CHUNK_ELEMS // row_len)
+    ranges = [(r0, min(n_rows, r0 + step)) for r0 in range(0, n_rows, step)]
+    return ranges[part::n_parts]
