@@ -3,10 +3,12 @@
 
 A "step" is one pass of the whole hot path over one batch: the in-place masked softmax over the
 attention scores followed by the fused add-bias-LayerNorm, both launched through the C ABI on one
-HIP stream.  The headline workload is the benchmark's configs[1] (BERT-base serving batch, fp32).
+HIP stream.  The headline workload is the benchmark's configs[3] (rows of 4096 fp32 values), the largest
+configuration that fits one GPU; configs[1] (BERT-base serving batch), the smallest timed one and the stated worst
+case, is reported with every other configuration under "per_config".
 
-Timing is "cold": the step cycles through enough independent buffer sets (> 512 MB in total, twice
-the 256 MB last-level cache) that every launch streams its operands from HBM.  Inputs are resident
+Timing is "cold": every timing loop cycles through enough independent buffer sets (at least 640 MB of streamed
+tensors in total, more than twice the 256 MB last-level cache) that every launch streams its operands from HBM.  Inputs are resident
 in HBM before the timed region starts.  The metric is achieved HBM GB/s over the algorithmic bytes
 (softmax 2*s*N + mask, LayerNorm 3*s*M + 3*s*hidden), reported against the 8 TB/s peak.
 
@@ -31,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for a plain copy of known size); written from the counter runs described beside it.
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic_pmc_configs1-4.json")
 COLD_BYTES = 640 << 20       # rotate over at least this many bytes of operands
-MAX_SETS = 24
+MAX_SETS = 48                # config 1's softmax tensor is 15.7 MB: 41 sets reach COLD_BYTES
 
 
 def parse_args():
@@ -39,13 +41,16 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="BASELINE.json config index of the headline workload")
+    ap.add_argument("--config", type=int, default=3, help="BASELINE.json config index of the headline workload")
+    ap.add_argument("--seed", type=int, default=0, help="offset added to the seed of the device-side input generator")
+    ap.add_argument("--dtype", choices=["config", "f32", "f16"], default="config",
+                    help="storage type of the headline workload's tensors (default: the configuration's own)")
     ap.add_argument("--per-config", type=int, default=1, help="also time every config's two kernels (0/1)")
     ap.add_argument("--cpu-baseline", type=int, default=1, help="time the CPU oracle on a bounded sample (0/1)")
     ap.add_argument("--launch", choices=["auto", "graph", "eager"], default="auto",
                     help="graph replay, eager stream launches, or (auto) graph for microsecond kernels and the faster "
                          "of the two for kernels long enough to hide the host's launch cost")
-    ap.add_argument("--kernel-iters", type=int, default=100, help="launches per kernel timing")
+    ap.add_argument("--kernel-iters", type=int, default=100, help="launches per kernel timing loop")
     ap.add_argument("--traffic-probe", type=int, default=0,
                     help="run only: one plain copy of a known size, then N cold launches of each kernel of --config; "
                          "meant to run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
@@ -109,27 +114,40 @@ class KernelSets:
 
 
 AUTO_EAGER_FROM_MS = 0.015  # kernels at least this long hide the host's cost of an eager launch
+HEADLINE_REPS = 5  # repetitions of the K-step headline measurement; the median one is reported
+TIMING_LOOPS = 3  # every figure is the MEDIAN of this many timing loops (each loop averages all its launches)
+
+
+class Timing:
+    """ms: median over the timing loops of the per-launch average; ms_min: the fastest loop; n: launches per loop."""
+
+    def __init__(self, loops_ms, n, mode):
+        self.loops_ms = sorted(loops_ms)
+        self.ms = float(np.median(self.loops_ms))
+        self.ms_min = self.loops_ms[0]
+        self.n, self.mode = n, mode
 
 
 def time_launches(torch, stream, fn, iters, period, launch):
-    """Average duration (ms) of fn(i) over `iters` launches on `stream`, by HIP events on that stream.
+    """Per-launch duration of fn(i) over `iters` launches on `stream`, by HIP events on that stream.
 
     With launch == "graph", `period` consecutive launches (one full rotation over the buffer sets) are
     captured into a HIP graph that is replayed; this removes host launch cost from kernels that run
     for a few microseconds.  Kernels of tens of microseconds hide that cost by themselves, and a graph's
     kernel nodes then cost more per launch than plain stream launches (about 1.5 us each, measured; the
     profiler's per-dispatch durations agree with the eager figure), so "auto" times such kernels both
-    ways and keeps the faster.  Returns (ms_per_launch, launches_timed, mode)."""
+    ways and keeps the mode whose median is lower.  Returns a Timing."""
     if launch == "auto":
         best = _time_launches(torch, stream, fn, iters, period, "graph")
-        if best[0] >= AUTO_EAGER_FROM_MS:
+        if best.ms >= AUTO_EAGER_FROM_MS:
             eager = _time_launches(torch, stream, fn, iters, period, "eager")
-            best = min(best, eager, key=lambda r: r[0])
+            best = min(best, eager, key=lambda r: r.ms)
         return best
     return _time_launches(torch, stream, fn, iters, period, launch)
 
 
-TIMING_LOOPS = 3  # each figure is the fastest of this many timing loops (every loop averages all its launches)
+def time_ms(*args):
+    return time_launches(*args).ms
 
 
 def _time_launches(torch, stream, fn, iters, period, launch):
@@ -150,7 +168,7 @@ def _time_launches(torch, stream, fn, iters, period, launch):
             except Exception as exc:  # capture not possible: fall back to eager launches, say so
                 print(f"[bench] graph capture failed ({exc!r}); eager launches", file=sys.stderr)
                 graph = None
-        best = None
+        loops = []
         for _ in range(TIMING_LOOPS):
             if graph is not None:
                 reps = max(1, -(-iters // period))
@@ -169,9 +187,8 @@ def _time_launches(torch, stream, fn, iters, period, launch):
                 stop.record(stream)
                 stream.synchronize()
                 n = iters
-            ms = start.elapsed_time(stop) / n
-            best = ms if best is None else min(best, ms)
-    return best, n, mode
+            loops.append(start.elapsed_time(stop) / n)
+    return Timing(loops, n, mode)
 
 
 COPY_PROBE_BYTES = 256 << 20
@@ -217,7 +234,7 @@ def elementwise_table(torch, tb, stream, launch, iters):
         outs = [torch.empty_like(x) for x in xs]
         bias = torch.randn((4 * hidden,), generator=gen, device="cuda").to(tdt)
         for approx, name in ((False, "add_bias_gelu_erf"), (True, "add_bias_gelu_tanh")):
-            ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_gelu(xs[i % n], bias, approx, outs[i % n],
+            ms = time_ms(torch, stream, lambda i: tb.turbo_add_bias_gelu(xs[i % n], bias, approx, outs[i % n],
                                                                                   stream=stream), iters, n, launch)
             nbytes = 2 * es * n_el + es * 4 * hidden
             entry[name] = {"shape": [B * S, 4 * hidden], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
@@ -228,7 +245,7 @@ def elementwise_table(torch, tb, stream, launch, iters):
         xs, n = sets((B, S, 3, H, D), 2 * es * n_el)
         outs = [torch.empty((3, B, H, S, D), device="cuda", dtype=tdt) for _ in xs]
         b3 = torch.randn((3, H, D), generator=gen, device="cuda").to(tdt)
-        ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_split_heads(xs[i % n], b3, outs[i % n],
+        ms = time_ms(torch, stream, lambda i: tb.turbo_add_bias_split_heads(xs[i % n], b3, outs[i % n],
                                                                                      stream=stream), iters, n, launch)
         nbytes = 2 * es * n_el + es * 3 * hidden
         entry["add_bias_split_heads"] = {"shape": [B, S, 3, H, D], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
@@ -236,7 +253,7 @@ def elementwise_table(torch, tb, stream, launch, iters):
                                          "cold_frac_of_8TBs": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
         ys = [o[0] for o in outs]  # [B,H,S,D], contiguous
         ms_out = [torch.empty((B, S, H, D), device="cuda", dtype=tdt) for _ in ys]
-        ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_merge_heads(ys[i % n], ms_out[i % n], stream=stream),
+        ms = time_ms(torch, stream, lambda i: tb.turbo_merge_heads(ys[i % n], ms_out[i % n], stream=stream),
                                  iters, n, launch)
         nbytes = 2 * es * B * S * hidden
         entry["merge_heads"] = {"shape": [B, H, S, D], "bytes": nbytes, "cold_us": round(ms * 1e3, 2),
@@ -266,7 +283,7 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
             ("layernorm", lambda i: tb.turbo_add_bias_layernorm_varlen(
                 view(ks.x[i % ks.n_ln_sets]), view(ks.res[i % ks.n_ln_sets]), ks.bias, ks.gamma, ks.beta, lens, spec.eps,
                 view(ks.out[i % ks.n_ln_sets]), stream=stream), ks.n_ln_sets, ln_bytes, ks.layernorm_bytes)):
-        ms, _, _ = time_launches(torch, stream, fn, iters, per, launch)
+        ms = time_ms(torch, stream, fn, iters, per, launch)
         rows[name] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1),
                       "padded_bytes": padded_bytes, "real_fraction_of_padded_bytes": round(nbytes / padded_bytes, 3)}
     # the same requests with no padding in memory at all (row-packed): softmax blocks [H, n, n] one after the other,
@@ -279,7 +296,7 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
     packed = [torch.randn(n_scores, generator=gen, device="cuda") * spec.score_std for _ in range(n_sets)]
     cu_d, off_d = torch.from_numpy(cu).cuda(), torch.from_numpy(off).cuda()
     max_len = int(spec.lengths.max())
-    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_masked_softmax_packed(
+    ms = time_ms(torch, stream, lambda i: tb.turbo_masked_softmax_packed(
         packed[i % n_sets], cu_d, off_d, H, total_tokens, max_len, spec.scale, stream=stream), iters, n_sets, launch)
     nbytes = 2 * es * n_scores + 12 * (B + 1)
     rows["softmax_packed"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1)}
@@ -287,7 +304,7 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
     n_sets = int(max(2, min(MAX_SETS, -(-COLD_BYTES // (3 * es * total_tokens * hid)))))
     xs, rs = ([torch.randn((total_tokens, hid), generator=gen, device="cuda") for _ in range(n_sets)] for _ in range(2))
     outs = [torch.empty_like(x) for x in xs]
-    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_add_bias_layernorm_dt(
+    ms = time_ms(torch, stream, lambda i: tb.turbo_add_bias_layernorm_dt(
         xs[i % n_sets], rs[i % n_sets], ks.bias, ks.gamma, ks.beta, spec.eps, outs[i % n_sets], stream=stream), iters, n_sets, launch)
     nbytes = 3 * es * total_tokens * hid + 3 * es * hid
     rows["layernorm_packed"] = {"cold_us": round(ms * 1e3, 2), "bytes_moved": nbytes, "GBs_of_bytes_moved": round(nbytes / ms / 1e6, 1)}
@@ -297,7 +314,7 @@ def varlen_table(torch, tb, wl, stream, launch, iters):
     # config 4 (GPT-2-medium, fp16) through the causal entry point: no mask tensor, keys above the diagonal unread
     spec4 = wl.config_spec(4)
     k4 = KernelSets(spec4, torch, tb, wl)
-    ms, _, _ = time_launches(torch, stream, lambda i: tb.turbo_masked_softmax_causal(k4.scores[i % k4.n_sm_sets], None, None,
+    ms = time_ms(torch, stream, lambda i: tb.turbo_masked_softmax_causal(k4.scores[i % k4.n_sm_sets], None, None,
                                                                                   spec4.scale, stream=stream),
                              iters, k4.n_sm_sets, launch)
     n_rows, Sq, Sk = spec4.B * spec4.H * spec4.Sq, spec4.Sq, spec4.Sk
@@ -323,7 +340,7 @@ def scheduler_table(torch, tb, wl, stream, launch, iters):
         spec = wl.ConfigSpec(2, f"b{b}-len{L}", np.float32, b, base.H, L, L, base.score_std, base.scale, "key",
                              b * L, base.hidden, base.eps, lengths=np.full(b, L, dtype=np.int64))
         k = KernelSets(spec, torch, tb, wl, max_sets=8)
-        ms, _, _ = time_launches(torch, stream, lambda i: k.step(i, stream), iters, max(k.n_sm_sets, k.n_ln_sets), launch)
+        ms = time_ms(torch, stream, lambda i: k.step(i, stream), iters, max(k.n_sm_sets, k.n_ln_sets), launch)
         del k
         return ms
 
@@ -346,31 +363,35 @@ def scheduler_table(torch, tb, wl, stream, launch, iters):
     }
 
 
-def cpu_baseline(spec, wl, budget_s=10.0):
-    """The oracle as it stands, on the headline workload, on the host cores of this machine."""
+def cpu_baseline(spec, wl, torch, tb, budget_s=16.0):
+    """The oracle as it stands, on a bounded sample of the headline workload, on the host cores of this machine; the HIP
+    path runs on the same sample and its largest deviation from the oracle is reported beside the timing."""
     from oracle import turbo_oracle as orc
     cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     cores = max(1, min(16, cores))
-    sc, lc = wl.softmax_case(spec), wl.layernorm_case(spec)
-    # bound the sample: at most ~8M elements of each tensor (whole rows)
-    max_rows_sm = max(1, (8 << 20) // spec.Sk)
+    # bound the sample: about 16M elements of each tensor (whole rows, from the start of the tensor)
     n_rows_sm = spec.B * spec.H * spec.Sq
-    take_sm = min(n_rows_sm, max_rows_sm)
-    s2 = sc.scores.reshape(n_rows_sm, spec.Sk)[:take_sm].astype(np.float64).reshape(1, 1, take_sm, spec.Sk)
-    take_ln = min(spec.rows, max(1, (8 << 20) // spec.hidden))
-    x, r = lc.x[:take_ln].astype(np.float64), lc.residual[:take_ln].astype(np.float64)
+    take_sm = min(n_rows_sm, max(1, (16 << 20) // spec.Sk))
+    take_ln = min(spec.rows, max(1, (16 << 20) // spec.hidden))
+    whole_sm, whole_ln = take_sm == n_rows_sm, take_ln == spec.rows
+    # the sample is drawn with the workload's distributions at the sample's own shape (the tensors of the full
+    # workload are gigabytes on the host); rows are independent, so a sample of rows is the same work per row
+    sample = wl.ConfigSpec(spec.index, spec.name + "-sample", spec.dtype, 1, 1, take_sm, spec.Sk, spec.score_std, spec.scale,
+                           "none", take_ln, spec.hidden, spec.eps)
+    sc, lc = wl.softmax_case(sample), wl.layernorm_case(sample)
+    s64 = sc.scores.astype(np.float64)
+    x, r = lc.x.astype(np.float64), lc.residual.astype(np.float64)
     b, g, be = (v.astype(np.float64) for v in (lc.bias, lc.gamma, lc.beta))
     es = sc.scores.dtype.itemsize
     bytes_per_pass = 2 * es * take_sm * spec.Sk + 3 * es * take_ln * spec.hidden
 
     def one_pass():
-        orc.masked_softmax(s2, None, 0, 0, sc.scale)
-        orc.add_bias_layernorm(x, r, b, g, be, lc.eps)
+        return orc.masked_softmax(s64, None, 0, 0, sc.scale), orc.add_bias_layernorm(x, r, b, g, be, lc.eps)
 
     out = {}
     for label, threads in (("all", cores), ("one", 1)):
         orc.set_threads(threads)
-        one_pass()
+        want = one_pass()
         t0 = time.perf_counter()
         n = 0
         while True:
@@ -381,13 +402,48 @@ def cpu_baseline(spec, wl, budget_s=10.0):
         dt = time.perf_counter() - t0
         out[label] = bytes_per_pass * n / dt / 1e9
     orc.set_threads(1)
+
+    # the HIP path on the same sample, against the oracle's output
+    s_dev = torch.from_numpy(sc.scores).cuda()
+    tb.turbo_masked_softmax_ex(s_dev, None, 0, 0, sc.scale)
+    o_dev = torch.empty((take_ln, spec.hidden), device="cuda", dtype=s_dev.dtype)
+    tb.turbo_add_bias_layernorm_dt(*(torch.from_numpy(v).cuda() for v in (lc.x, lc.residual, lc.bias, lc.gamma, lc.beta)),
+                                   lc.eps, o_dev)
+    torch.cuda.synchronize()
+    errs = {}
+    for name, got, ref in (("softmax", s_dev.cpu().numpy().astype(np.float64), want[0]),
+                           ("layernorm", o_dev.cpu().numpy().astype(np.float64), want[1])):
+        err = np.abs(got - ref)
+        big = np.abs(ref) >= 0.1  # where the relative error is the meaningful one
+        errs[name] = {"max_abs_err": float(err.max()),
+                      "max_rel_err_where_ref_ge_0.1": float((err[big] / np.abs(ref[big])).max()) if big.any() else None}
     return {
         "value": round(out["all"], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": (f"{take_sm} of {n_rows_sm} softmax rows x {spec.Sk} and {take_ln} of {spec.rows} LayerNorm rows x "
-                   f"{spec.hidden} of the headline workload, fp64 oracle incl. its output writes, repeated for "
-                   f"{budget_s / 2:.0f} s; mask omitted in the sample"),
+        "sample": (f"{'all' if whole_sm else 'the first'} {take_sm} of {n_rows_sm} softmax rows x {spec.Sk} and "
+                   f"{'all' if whole_ln else 'the first'} {take_ln} of {spec.rows} LayerNorm rows x {spec.hidden} of the "
+                   f"headline workload's shape and distributions, fp64 oracle incl. its output writes, repeated for "
+                   f"{budget_s / 2:.0f} s per thread count; bytes counted as for the GPU (storage type); mask omitted"),
         "one_core_value": round(out["one"], 3),
+        "hip_path_vs_oracle_on_the_sample": errs,
     }
+
+
+def roofline_entry(name, nbytes, t, period, traffic):
+    achieved = nbytes / (t.ms * 1e-3) / 1e9
+    entry = {
+        "bound": "hbm", "kernel": name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "algorithmic_bytes_per_launch": nbytes, "avg_launch_us": round(t.ms * 1e3, 3),
+        "fastest_loop_us": round(t.ms_min * 1e3, 3), "launches": t.n,
+        "timing": f"one HIP event pair around {t.n} back-to-back {t.mode} launches on the launch stream, median of "
+                  f"{TIMING_LOOPS} such loops, cold (rotating {period} buffer sets)",
+    }
+    if traffic and traffic.get("algorithmic_bytes") == nbytes:
+        entry["traffic"] = traffic["traffic_bytes"]
+        entry["traffic_measured_in_this_run"] = False
+        entry["traffic_source"] = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (--traffic-probe), "
+                                   "summarised in profiles/; not re-measured by this run")
+    return entry
 
 
 def main():
@@ -409,14 +465,17 @@ def main():
     stream = torch.cuda.Stream()
 
     spec = wl.config_spec(args.config)
-    ks = KernelSets(spec, torch, tb, wl)
+    if args.dtype != "config":
+        import dataclasses
+        spec = dataclasses.replace(spec, dtype=np.float32 if args.dtype == "f32" else np.float16)
+    ks = KernelSets(spec, torch, tb, wl, seed=args.seed)
     if args.traffic_probe:
         traffic_probe(torch, ks, stream, args.traffic_probe)
         return
     period = max(ks.n_sm_sets, ks.n_ln_sets)
     step_bytes = ks.softmax_bytes + ks.layernorm_bytes
 
-    # ---- headline: exactly K whole steps, wall clock bracketed by synchronisation ----
+    # ---- headline: exactly K whole steps per repetition, wall clock bracketed by synchronisation ----
     steps = args.steps
     with torch.cuda.stream(stream):
         graph, graph_rem, mode = None, None, "eager"
@@ -446,59 +505,67 @@ def main():
             except Exception as exc:
                 print(f"[bench] graph capture failed ({exc!r}); eager launches", file=sys.stderr)
                 graph, graph_rem, mode = None, None, "eager"
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if mode == "graph":
-            for _ in range(reps):
-                graph.replay()
-            if graph_rem is not None:
-                graph_rem.replay()
-        else:
-            for i in range(steps):
-                ks.step(i, stream)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / steps
+
+        def k_steps():
+            """Exactly K steps: wall clock between two device synchronisations, and a HIP event pair on the stream."""
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev0.record(stream)
+            if mode == "graph":
+                for _ in range(reps):
+                    graph.replay()
+                if graph_rem is not None:
+                    graph_rem.replay()
+            else:
+                for i in range(steps):
+                    ks.step(i, stream)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+        # a K of 20 is a few milliseconds of work: the K steps are timed HEADLINE_REPS times and the median
+        # repetition is reported, so one slow host wake-up cannot decide the figure
+        runs = sorted(k_steps() for _ in range(HEADLINE_REPS))
+    ms_per_step, ms_per_step_events = runs[len(runs) // 2]
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- dominant kernel of the headline workload: live HIP-event timing on the launch stream ----
-    dom = "softmax" if ks.softmax_bytes >= ks.layernorm_bytes else "layernorm"
-    dom_fn = (lambda i: ks.softmax(i, stream)) if dom == "softmax" else (lambda i: ks.layernorm(i, stream))
-    dom_period = ks.n_sm_sets if dom == "softmax" else ks.n_ln_sets
-    dom_bytes = ks.softmax_bytes if dom == "softmax" else ks.layernorm_bytes
-    ms_dom, n_dom, dom_mode = time_launches(torch, stream, dom_fn, args.kernel_iters * 4, dom_period, args.launch)
-    achieved = dom_bytes / (ms_dom * 1e-3) / 1e9
-    roofline = {
-        "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-        "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(ms_dom * 1e3, 3), "launches": n_dom,
-        "timing": f"one HIP event pair around {n_dom} back-to-back {dom_mode} launches on the launch stream (fastest of "
-                  f"{TIMING_LOOPS} such loops), cold "
-                  f"(rotating {dom_period} buffer sets)",
-    }
-
+    # ---- both kernels of the headline workload: live HIP-event timing on the launch stream ----
+    traffic = {}
     try:
         with open(TRAFFIC_JSON) as fh:
-            entry = json.load(fh).get(f"cfg{spec.index}_{dom}")
-        if entry and entry.get("algorithmic_bytes") == dom_bytes:
-            roofline["traffic"] = entry["traffic_bytes"]
-            roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/"
+            traffic = json.load(fh)
     except (OSError, ValueError):
         pass
+    t_sm = time_launches(torch, stream, lambda i: ks.softmax(i, stream), args.kernel_iters * 2, ks.n_sm_sets, args.launch)
+    t_ln = time_launches(torch, stream, lambda i: ks.layernorm(i, stream), args.kernel_iters * 2, ks.n_ln_sets, args.launch)
+    roof = {"softmax": roofline_entry("softmax", ks.softmax_bytes, t_sm, ks.n_sm_sets, traffic.get(f"cfg{spec.index}_softmax")),
+            "layernorm": roofline_entry("layernorm", ks.layernorm_bytes, t_ln, ks.n_ln_sets,
+                                        traffic.get(f"cfg{spec.index}_layernorm"))}
+    dom = "softmax" if ks.softmax_bytes >= ks.layernorm_bytes else "layernorm"
+    other = "layernorm" if dom == "softmax" else "softmax"
 
-    # ---- every config, both kernels, cold and warm ----
+    # ---- every config, both kernels, cold and warm, beside the plain stream of the same bytes ----
     per_config = []
+    empty_launch_us = None
     if args.per_config:
+        # a launch that moves 16 bytes: what one dispatch costs when launches run back to back
+        tiny = torch.zeros(4, device="cuda")
+        t_empty = time_launches(torch, stream, lambda i: tb.turbo_stream_probe(tiny, None, tiny, stream=stream),
+                                args.kernel_iters * 4, 40, "graph")
+        empty_launch_us = round(t_empty.ms * 1e3, 3)
         for idx in range(5):
             sp = wl.config_spec(idx)
-            k = ks if idx == args.config else KernelSets(sp, torch, tb, wl)
+            k = ks if (idx == args.config and args.dtype == "config") else KernelSets(sp, torch, tb, wl, seed=args.seed)
             row = {"config": idx, "name": sp.name, "dtype": "f32" if sp.dtype == np.float32 else "f16"}
-            for name, fn, per, nbytes, nrows in (
-                    ("softmax", lambda i, k=k: k.softmax(i, stream), k.n_sm_sets, k.softmax_bytes, k.softmax_rows),
-                    ("layernorm", lambda i, k=k: k.layernorm(i, stream), k.n_ln_sets, k.layernorm_bytes, sp.rows)):
+            for name, fn, per, nbytes, nrows, streamed in (
+                    ("softmax", lambda i, k=k: k.softmax(i, stream), k.n_sm_sets, k.softmax_bytes, k.softmax_rows,
+                     k.es * sp.B * sp.H * sp.Sq * sp.Sk),
+                    ("layernorm", lambda i, k=k: k.layernorm(i, stream), k.n_ln_sets, k.layernorm_bytes, sp.rows,
+                     3 * k.es * sp.rows * sp.hidden)):
                 iters = args.kernel_iters if nbytes < (256 << 20) else max(10, args.kernel_iters // 4)
-                ms_cold, _, md = time_launches(torch, stream, fn, iters, per, args.launch)
-                ms_warm, _, _ = time_launches(torch, stream, lambda i, fn=fn: fn(0), iters, 4, args.launch)
+                t_cold = time_launches(torch, stream, fn, iters, per, args.launch)
+                t_warm = time_launches(torch, stream, lambda i, fn=fn: fn(0), iters, 4, args.launch)
                 # the plain stream of the same bytes, mix and buffers: in-place copy for softmax, out = x + residual
                 # for LayerNorm (turbo_stream_probe, same access shape as the library's element-wise kernels)
                 if name == "softmax":
@@ -507,15 +574,20 @@ def main():
                 else:
                     probe = lambda i, k=k: tb.turbo_stream_probe(k.x[i % k.n_ln_sets], k.res[i % k.n_ln_sets],
                                                                  k.out[i % k.n_ln_sets], stream=stream)
-                ms_plain, _, _ = time_launches(torch, stream, probe, iters, per, args.launch)
+                t_plain = time_launches(torch, stream, probe, iters, per, args.launch)
+                rotated = per * streamed
                 row[name] = {
                     "bytes": nbytes, "rows": nrows,
-                    "cold_us": round(ms_cold * 1e3, 2), "cold_GBs": round(nbytes / ms_cold / 1e6, 1),
-                    "cold_frac_of_8TBs": round(nbytes / ms_cold / 1e6 / HBM_PEAK_GBS, 4),
-                    "cold_rows_per_s": round(nrows / (ms_cold * 1e-3), 1),
-                    "warm_us": round(ms_warm * 1e3, 2), "warm_GBs": round(nbytes / ms_warm / 1e6, 1),
-                    "plain_stream_us": round(ms_plain * 1e3, 2), "speed_vs_plain_stream": round(ms_plain / ms_cold, 3),
-                    "launch": md, "buffer_sets": per,
+                    "cold_us": round(t_cold.ms * 1e3, 2), "cold_us_fastest_loop": round(t_cold.ms_min * 1e3, 2),
+                    "cold_GBs": round(nbytes / t_cold.ms / 1e6, 1),
+                    "cold_frac_of_8TBs": round(nbytes / t_cold.ms / 1e6 / HBM_PEAK_GBS, 4),
+                    "cold_rows_per_s": round(nrows / (t_cold.ms * 1e-3), 1),
+                    "warm_us": round(t_warm.ms * 1e3, 2), "warm_GBs": round(nbytes / t_warm.ms / 1e6, 1),
+                    "plain_stream_us": round(t_plain.ms * 1e3, 2), "speed_vs_plain_stream": round(t_plain.ms / t_cold.ms, 3),
+                    "launch": t_cold.mode, "plain_stream_launch": t_plain.mode, "buffer_sets": per,
+                    "rotation_bytes": rotated,
+                    "regime": "cold (rotation exceeds twice the 256 MB last-level cache)" if rotated >= (512 << 20)
+                              else "cache-resident: the tensors are too small to rotate out of the last-level cache",
                 }
             per_config.append(row)
             if k is not ks:
@@ -531,13 +603,19 @@ def main():
             "workload": f"configs[{spec.index}] {spec.name}: softmax [{spec.B},{spec.H},{spec.Sq},{spec.Sk}] in place + "
                         f"add-bias-LayerNorm [{spec.rows},{spec.hidden}]",
             "bytes_per_step": step_bytes, "launch": mode, "regime": f"cold, rotating {period} buffer sets",
-            "frac_of_8TBs": round(value / HBM_PEAK_GBS, 4),
+            "frac_of_8TBs": round(value / HBM_PEAK_GBS, 4), "seed": args.seed,
+            "timing": f"wall clock between device synchronisations around exactly {steps} steps; median of {HEADLINE_REPS} "
+                      f"such repetitions",
+            "ms_per_step_by_hip_events": round(ms_per_step_events, 6),
+            "ms_per_step_all_repetitions": [round(r[0], 6) for r in runs],
         },
-        "roofline": roofline,
+        "roofline": roof[dom],
+        "roofline_other_kernel": roof[other],
     }
     if args.cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(spec, wl)
+        result["cpu_baseline"] = cpu_baseline(spec, wl, torch, tb)
     if per_config:
+        result["empty_launch_us"] = empty_launch_us
         result["per_config"] = per_config
         result["elementwise"] = elementwise_table(torch, tb, stream, args.launch, max(20, args.kernel_iters // 2))
         result["length_aware_config2"] = varlen_table(torch, tb, wl, stream, args.launch, max(20, args.kernel_iters // 2))

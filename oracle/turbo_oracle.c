@@ -157,8 +157,8 @@ void oracle_welford_merge(double na, double mean_a, double m2_a, double nb, doub
     *m2 = m2_a + m2_b + d * d * (na * nb / nt);
 }
 
-/* ---- element-wise fused kernels (Section 4.1.1: "fused activation functions and fused transpose
- * operations are composed of element-wise operations") ------------------------------------------------
+/* ---- element-wise fused kernels (Section 4.1.1 counts the fused activations and the fused transposes as the
+ * non-GEMM kernels that are purely element-wise) ---------------------------------------------------------
  * The paper names the two kinds but prints no formula or layout.  Readings taken here:
  *   - the activation is GELU, the feed-forward activation of the BERT family the paper evaluates:
  *     gelu(t) = t * Phi(t), Phi the standard normal distribution function (approximate = 0), or its

@@ -3,10 +3,12 @@
 // TURBO_ERR_LAUNCH is reported without a GPU.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstring>
 
 #include "../../include/turbo_reduce.h"
+#include "../../include/turbo_reduce_testing.h"
 #include "elementwise_kernels.h"
 #include "layernorm_kernels.h"
 #include "packed_kernels.h"
@@ -15,11 +17,23 @@
 
 namespace {
 
-turbo::Overrides g_ovr;
+// Process-wide switches of the testing hooks (turbo_reduce_testing.h).  Relaxed atomics: a test flips them between
+// calls, never during one; the atomics only keep a concurrent reader free of a data race.
+std::atomic<int> g_ovr_value[TURBO_OVR_COUNT_] = {{-1}, {-1}, {-1}, {-1}};
+
+turbo::Overrides current_overrides() {
+    turbo::Overrides o;
+    o.path = g_ovr_value[TURBO_OVR_PATH].load(std::memory_order_relaxed);
+    o.max_vec_bytes = g_ovr_value[TURBO_OVR_MAX_VEC_BYTES].load(std::memory_order_relaxed);
+    o.grid_waves = g_ovr_value[TURBO_OVR_GRID_WAVES].load(std::memory_order_relaxed);
+    o.block_waves = g_ovr_value[TURBO_OVR_BLOCK_WAVES].load(std::memory_order_relaxed);
+    return o;
+}
 
 constexpr int kMaxRows = 0x7FFF0000;  // leaves headroom for tile rounding in 32-bit row indices
-constexpr int kMaxDevices = 64;
-int g_num_cus[kMaxDevices];
+// Compute units per device, asked once per device.  Two threads that race on the first call both store the same
+// number, so relaxed atomics are enough.
+std::atomic<int> g_num_cus[turbo::kMaxDevices];
 
 int elem_size_of(int dtype) { return dtype == TURBO_F32 ? 4 : dtype == TURBO_F16 ? 2 : 0; }
 
@@ -38,31 +52,26 @@ long long stride_alignment(long long stride) {
     return v & (~v + 1);
 }
 
-int current_num_cus(int* out) {
+// The current device and its compute-unit count.
+int current_device(turbo::LaunchCfg* lc) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return TURBO_ERR_LAUNCH;
-    if (dev < 0 || dev >= kMaxDevices) {
-        int n = 0;
+    const bool cached = dev >= 0 && dev < turbo::kMaxDevices;
+    int n = cached ? g_num_cus[dev].load(std::memory_order_relaxed) : 0;
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             return TURBO_ERR_LAUNCH;
-        *out = n;
-        return TURBO_OK;
+        if (cached) g_num_cus[dev].store(n, std::memory_order_relaxed);
     }
-    if (g_num_cus[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return TURBO_ERR_LAUNCH;
-        g_num_cus[dev] = n;
-    }
-    *out = g_num_cus[dev];
+    lc->device = dev;
+    lc->num_cus = n;
     return TURBO_OK;
 }
 
-turbo::LaunchCfg launch_cfg(int num_cus) {
-    turbo::LaunchCfg lc;
-    lc.num_cus = num_cus;
-    lc.waves_per_cu = g_ovr.grid_waves > 0 ? (g_ovr.grid_waves > (1 << 20) ? (1 << 22) : g_ovr.grid_waves * 4) : 0;
-    return lc;
+int launch_cfg(const turbo::Overrides& ovr, turbo::LaunchCfg* lc) {
+    if (int st = current_device(lc)) return st;
+    lc->waves_per_cu = ovr.grid_waves > 0 ? (ovr.grid_waves > (1 << 20) ? (1 << 22) : ovr.grid_waves * 4) : 0;
+    return TURBO_OK;
 }
 
 int softmax_impl(void* scores, const void* mask, long long msb, long long msq, const int* q_lengths,
@@ -85,7 +94,7 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
         align_elems = min_ll(align_elems, stride_alignment(msb));
         align_elems = min_ll(align_elems, stride_alignment(msq));
     }
-    turbo::Overrides ovr = g_ovr;
+    turbo::Overrides ovr = current_overrides();
     if (k_lengths != nullptr || q_lengths != nullptr || causal) {  // per-row key counts: the kernels need their bounds checks
         if (reinterpret_cast<uintptr_t>(k_lengths) % 4 != 0 || reinterpret_cast<uintptr_t>(q_lengths) % 4 != 0)
             return TURBO_ERR_ALIGN;
@@ -111,9 +120,8 @@ int softmax_impl(void* scores, const void* mask, long long msb, long long msq, c
     a.div_rows_per_batch = turbo::make_fastdiv((unsigned)((long long)H * Sq));
     a.div_sq = turbo::make_fastdiv((unsigned)Sq);
 
-    int num_cus = 0;
-    if (int st = current_num_cus(&num_cus)) return st;
-    const turbo::LaunchCfg lc = launch_cfg(num_cus);
+    turbo::LaunchCfg lc;
+    if (int st = launch_cfg(ovr, &lc)) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipError_t err = dtype == TURBO_F32 ? turbo::launch_softmax_f32(plan, a, lc, s)
                                         : turbo::launch_softmax_f16(plan, a, lc, s);
@@ -134,7 +142,8 @@ int layernorm_impl(const void* x, const void* residual, const void* bias, const 
         if (reinterpret_cast<uintptr_t>(p) % es != 0) return TURBO_ERR_ALIGN;
         align_elems = min_ll(align_elems, byte_alignment(p) / es);
     }
-    const turbo::Plan plan = turbo::make_plan(hidden, es, align_elems, rows, turbo::kLayerNormLimits, g_ovr);
+    const turbo::Overrides ovr = current_overrides();
+    const turbo::Plan plan = turbo::make_plan(hidden, es, align_elems, rows, turbo::kLayerNormLimits, ovr);
 
     turbo::LayerNormArgs a;
     a.x = x;
@@ -151,9 +160,8 @@ int layernorm_impl(const void* x, const void* residual, const void* bias, const 
     a.S = S;
     a.div_s = turbo::make_fastdiv((unsigned)S);
 
-    int num_cus = 0;
-    if (int st = current_num_cus(&num_cus)) return st;
-    const turbo::LaunchCfg lc = launch_cfg(num_cus);
+    turbo::LaunchCfg lc;
+    if (int st = launch_cfg(ovr, &lc)) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipError_t err = dtype == TURBO_F32 ? turbo::launch_layernorm_f32(plan, a, lc, s)
                                         : turbo::launch_layernorm_f16(plan, a, lc, s);
@@ -175,8 +183,9 @@ int gelu_impl(const void* x, const void* bias, int rows, int hidden, int approxi
         if (reinterpret_cast<uintptr_t>(p) % es != 0) return TURBO_ERR_ALIGN;
         align_elems = min_ll(align_elems, byte_alignment(p) / es);
     }
+    const turbo::Overrides ovr = current_overrides();
     int vec = full_vec;
-    if (g_ovr.max_vec_bytes >= es && g_ovr.max_vec_bytes < 16) vec = 1;  // testing hook: the narrow kernel
+    if (ovr.max_vec_bytes >= es && ovr.max_vec_bytes < 16) vec = 1;  // testing hook: the narrow kernel
     if (total < vec) vec = 1;
     const bool under_aligned = vec > 1 && align_elems % vec != 0;
 
@@ -192,7 +201,7 @@ int gelu_impl(const void* x, const void* bias, int rows, int hidden, int approxi
     a.rows = rows;
     a.hv = 0;
     a.div_ct = turbo::make_fastdiv(1);
-    a.force_flat = g_ovr.path == 2;  // testing hook, as for the head permutations
+    a.force_flat = ovr.path == 2;  // testing hook, as for the head permutations
     hipError_t err = turbo::launch_add_bias_gelu(a, es, vec, under_aligned, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }
@@ -215,8 +224,9 @@ int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, 
         if (reinterpret_cast<uintptr_t>(p) % es != 0) return TURBO_ERR_ALIGN;
         align_elems = min_ll(align_elems, byte_alignment(p) / es);
     }
+    const turbo::Overrides ovr = current_overrides();
     int vec = 16 / es;
-    if (g_ovr.max_vec_bytes >= es && g_ovr.max_vec_bytes < 16) vec = g_ovr.max_vec_bytes / es;
+    if (ovr.max_vec_bytes >= es && ovr.max_vec_bytes < 16) vec = ovr.max_vec_bytes / es;
     while (vec > 1 && (D % vec != 0 || align_elems % vec != 0)) vec >>= 1;
     if (total / vec > 0x7FFFFFFFll) return TURBO_ERR_SHAPE;
 
@@ -239,7 +249,7 @@ int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, 
     // grouped kernel: the unrolled dimension (n2 when walking the output, n1 when walking the input) must divide
     // evenly, and a bias is only supported when it does not depend on that dimension (input order)
     const int unrolled = out_order ? N2 : N1;
-    a.grouped = unrolled % turbo::kElemUnroll == 0 && !(bias != nullptr && out_order) && g_ovr.path != 2;
+    a.grouped = unrolled % turbo::kElemUnroll == 0 && !(bias != nullptr && out_order) && ovr.path != 2;
     a.div_n1u = turbo::make_fastdiv((unsigned)(N1 % turbo::kElemUnroll == 0 ? N1 / turbo::kElemUnroll : 1));
     a.div_n2u = turbo::make_fastdiv((unsigned)(N2 % turbo::kElemUnroll == 0 ? N2 / turbo::kElemUnroll : 1));
     hipError_t err = turbo::launch_permute_heads(a, es, vec, reinterpret_cast<hipStream_t>(stream));
@@ -325,12 +335,13 @@ int turbo_masked_softmax_packed(void* scores, const int* cu_seqlens, const long 
     a.H = H;
     a.n_rows = H * total_tokens;
     a.scale = scale;
-    int num_cus = 0;
-    if (int st = current_num_cus(&num_cus)) return st;
+    const turbo::Overrides ovr = current_overrides();
+    turbo::LaunchCfg lc;
+    if (int st = launch_cfg(ovr, &lc)) return st;
     // testing hooks: TURBO_OVR_PATH = 0 selects the kernel that gives every row a whole wavefront (the one batches of
     // 64 or more requests use), TURBO_OVR_GRID_WAVES caps the grid
-    const hipError_t err = turbo::launch_softmax_packed(a, es, max_len, num_cus, g_ovr.grid_waves > 0 ? g_ovr.grid_waves : 0,
-                                                        g_ovr.path == 0, reinterpret_cast<hipStream_t>(stream));
+    const hipError_t err = turbo::launch_softmax_packed(a, es, max_len, lc.num_cus, ovr.grid_waves > 0 ? ovr.grid_waves : 0,
+                                                        ovr.path == 0, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? TURBO_OK : TURBO_ERR_LAUNCH;
 }
 
@@ -347,13 +358,9 @@ const char* turbo_status_string(int status) {
 }
 
 int turbo_set_override(int key, int value) {
-    switch (key) {
-        case TURBO_OVR_PATH: g_ovr.path = value; return TURBO_OK;
-        case TURBO_OVR_MAX_VEC_BYTES: g_ovr.max_vec_bytes = value; return TURBO_OK;
-        case TURBO_OVR_GRID_WAVES: g_ovr.grid_waves = value; return TURBO_OK;
-        case TURBO_OVR_BLOCK_WAVES: g_ovr.block_waves = value; return TURBO_OK;
-    }
-    return TURBO_ERR_SHAPE;
+    if (key < 0 || key >= TURBO_OVR_COUNT_) return TURBO_ERR_SHAPE;
+    g_ovr_value[key].store(value, std::memory_order_relaxed);
+    return TURBO_OK;
 }
 
 int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16, char* buf, int buf_len) {
@@ -362,7 +369,7 @@ int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16,
     if (es == 0) return TURBO_ERR_DTYPE;
     if ((op != 0 && op != 1) || rows <= 0 || row_len <= 0 || buf_len <= 0) return TURBO_ERR_SHAPE;
     const turbo::OpLimits& lim = op == 0 ? turbo::kSoftmaxLimits : turbo::kLayerNormLimits;
-    const turbo::Plan p = turbo::make_plan(row_len, es, aligned16 ? 16 / es : 1, rows, lim, g_ovr);
+    const turbo::Plan p = turbo::make_plan(row_len, es, aligned16 ? 16 / es : 1, rows, lim, current_overrides());
     turbo::describe_plan(p, buf, buf_len);
     return TURBO_OK;
 }

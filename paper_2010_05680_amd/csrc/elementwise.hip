@@ -62,12 +62,6 @@ hipError_t gelu_tv(const GeluArgs& a0, bool ua, hipStream_t s) {
     return hipGetLastError();
 }
 
-// The kernels that walk their output (the head merge) gather their input in pieces of D elements; they stream best
-// with few wavefronts resident.  An LDS allocation that the kernel never touches holds a compute unit at 3 workgroups:
-// +1.5..6 points of HBM peak on every merge shape measured (D = 32, 64, 128; S = 500..2048; both element types); the
-// kernels that walk their input are indifferent, bias + GELU loses.
-constexpr unsigned kGatherLdsLimit = 53000;
-
 template <typename T, int VEC>
 hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
     if (a.grouped) {
@@ -77,7 +71,7 @@ hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
             // with a bias the unrolled dimension must not enter the bias index: true for the split (input order)
             hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, true, false>), g, blk, 0, s, a);
         } else if (a.out_order) {
-            hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, false, true>), g, blk, kGatherLdsLimit, s, a);
+            hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, false, true>), g, blk, 0, s, a);
         } else {
             hipLaunchKernelGGL((permute_heads_grouped_kernel<T, VEC, false, false>), g, blk, 0, s, a);
         }
@@ -89,7 +83,7 @@ hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
         hipLaunchKernelGGL((permute_heads_kernel<T, VEC, true, false>), grid, block, 0, s, a);
     } else {
         if (a.out_order)
-            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, true>), grid, block, kGatherLdsLimit, s, a);
+            hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, true>), grid, block, 0, s, a);
         else
             hipLaunchKernelGGL((permute_heads_kernel<T, VEC, false, false>), grid, block, 0, s, a);
     }

@@ -35,7 +35,7 @@ struct GeluArgs {
 // infinite t finite in the product), with a branch-free tail of the normal distribution:  Phi(-u) ~= 2^Q(u),  Q a polynomial.
 // log2 Phi(-u) is smooth and nearly quadratic, so Q needs degree 5 for binary16 outputs (the result stays within
 // 0.18 of the parity bound max(1e-6, 3e-3 |gelu|), rounding to binary16 included) and degree 8 for binary32 (0.04 of
-// max(1e-6, 1e-5 |gelu|)).  The constants are fitted by csrc/fit_gelu_phi.py.  The math library's erfc is exact to a
+// max(1e-6, 1e-5 |gelu|)).  The constants are fitted by fit_gelu_phi.py (beside build.py).  The math library's erfc is exact to a
 // few ulp but its range branches make this kernel ALU-bound (measured: 30 % of the HBM peak for binary16 storage);
 // this form costs DEGREE + 3 vector instructions and one transcendental per element.
 template <int DEGREE>
@@ -194,10 +194,17 @@ struct PermuteArgs {
     int out_order;  // 1: lanes walk the output tensor, 0: the input tensor
 };
 
+// The kernels that walk their output (the head merge) gather their input in pieces of D elements; they stream best
+// with few wavefronts resident, so they are built to hold a SIMD at 3 wavefronts (3 workgroups per compute unit):
+// +1.5..6 points of HBM peak on every merge shape measured (D = 32, 64, 128; S = 500..2048; both element types); the
+// kernels that walk their input are indifferent, bias + GELU loses.
+constexpr int kGatherWavesPerSimd = 3;
+
 // OUT_ORDER = false: lanes walk the input (reads fully coalesced, writes in D-element pieces);
 // OUT_ORDER = true : lanes walk the output (writes fully coalesced, reads in D-element pieces).
 template <typename T, int VEC, bool BIAS, bool OUT_ORDER>
-__global__ __launch_bounds__(kElemThreads) void permute_heads_kernel(PermuteArgs a) {
+__global__ __launch_bounds__(kElemThreads) __attribute__((amdgpu_waves_per_eu(1, OUT_ORDER ? kGatherWavesPerSimd : 8)))
+void permute_heads_kernel(PermuteArgs a) {
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
     T* out = reinterpret_cast<T*>(a.out);
@@ -262,7 +269,8 @@ __global__ __launch_bounds__(kElemThreads) void permute_heads_kernel(PermuteArgs
 //   OUT_ORDER = true  (merge): lanes walk [k][b][n2/U][n1][dv], u runs over n2 (adjacent in the input).
 // Needs N1 (resp. N2) to be a multiple of kElemUnroll; the host falls back to the flat kernel otherwise.
 template <typename T, int VEC, bool BIAS, bool OUT_ORDER>
-__global__ __launch_bounds__(kElemThreads) void permute_heads_grouped_kernel(PermuteArgs a) {
+__global__ __launch_bounds__(kElemThreads) __attribute__((amdgpu_waves_per_eu(1, OUT_ORDER ? kGatherWavesPerSimd : 8)))
+void permute_heads_grouped_kernel(PermuteArgs a) {
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
     T* out = reinterpret_cast<T*>(a.out);

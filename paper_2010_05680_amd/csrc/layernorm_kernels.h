@@ -13,6 +13,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "device_utils.h"
 #include "plan.h"
 #include "softmax_kernels.h"  // LaunchCfg, capped_grid, rows_in_flight_c
@@ -615,8 +617,12 @@ template <typename T, int VEC, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     // The kernel loops over rows with a fixed assignment of rows to workgroups, so the grid is a whole number of
     // "rounds" of what the chip holds at once: a partial last round would run with most compute units idle.
-    static int resident[kBlockMaxWaves + 1];  // workgroups of w wavefronts that fit one compute unit; 0 = not asked yet
-    int per_cu = resident[p.waves];
+    // Workgroups of w wavefronts of THIS kernel that one compute unit of device d holds; 0 = not asked yet.  One table per
+    // kernel instantiation, keyed by device and workgroup size.  Concurrent first calls store the same number, so
+    // relaxed atomics suffice.
+    static std::atomic<int> resident[kMaxDevices][kBlockMaxWaves + 1];
+    const bool cached = lc.device >= 0 && lc.device < kMaxDevices;
+    int per_cu = cached ? resident[lc.device][p.waves].load(std::memory_order_relaxed) : 0;
     if (per_cu == 0) {
         int n = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, layernorm_block_kernel<T, VEC, NV, RES, MODE>, 64 * p.waves, 0) !=
@@ -624,7 +630,8 @@ hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const L
             (void)hipGetLastError();
             n = 16 / p.waves;
         }
-        resident[p.waves] = per_cu = n;
+        per_cu = n;
+        if (cached) resident[lc.device][p.waves].store(n, std::memory_order_relaxed);
     }
     int grid;
     if (lc.waves_per_cu > 0) {

@@ -22,10 +22,7 @@ hipError_t packed_groups_tv(const PackedSoftmaxArgs& a, int max_len, int num_cus
     else if (per_lane <= 4)
         hipLaunchKernelGGL((softmax_packed_groups_kernel<T, VEC, 4>), grid, block, 0, s, a);
     else if (per_lane <= 8)
-        // Rows of 32 elements per lane stream best with at most five wavefronts per SIMD (element-aligned accesses like
-        // fewer of them in flight); the fp32 kernel's registers would allow six, so an LDS allocation that is not used
-        // holds the compute unit at five workgroups: 12 requests of 1000-2000 floats 474 -> 460 us.
-        hipLaunchKernelGGL((softmax_packed_groups_kernel<T, VEC, 8>), grid, block, sizeof(T) == 4 ? 32000 : 0, s, a);
+        hipLaunchKernelGGL((softmax_packed_groups_kernel<T, VEC, 8>), grid, block, 0, s, a);
     else if (per_lane <= 16)
         hipLaunchKernelGGL((softmax_packed_groups_kernel<T, VEC, 16>), grid, block, 0, s, a);
     else

@@ -300,9 +300,18 @@ __device__ __forceinline__ void packed_task(T* base, int n, int row0, int rows_b
     }
 }
 
+// Rows of 32 elements per lane stream best with at most five wavefronts per SIMD (element-aligned accesses like fewer of
+// them in flight); the fp32 kernel's registers would allow six, so that build is held at five: 12 requests of
+// 1000-2000 floats 474 -> 460 us.
+template <typename T, int NVMAX>
+constexpr int packed_groups_waves_per_simd() {
+    return (sizeof(T) == 4 && NVMAX == 8) ? 5 : 8;
+}
+
 // NVMAX: vectors per lane that the longest request needs (a power of two); longer requests are left untouched.
 template <typename T, int VEC, int NVMAX>
-__global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_groups_kernel(PackedSoftmaxArgs a) {
+__global__ __launch_bounds__(64 * kPackedWaves) __attribute__((amdgpu_waves_per_eu(1, packed_groups_waves_per_simd<T, NVMAX>())))
+void softmax_packed_groups_kernel(PackedSoftmaxArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave_id = (int)blockIdx.x * kPackedWaves + (int)(threadIdx.x >> 6);
     const int n_waves = (int)gridDim.x * kPackedWaves;

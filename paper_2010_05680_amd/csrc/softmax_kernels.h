@@ -45,7 +45,10 @@ struct SoftmaxArgs {
     FastDiv div_sq;              // Sq
 };
 
+constexpr int kMaxDevices = 64;  // devices with a slot in the per-device launch caches (others are asked every time)
+
 struct LaunchCfg {
+    int device;    // the current HIP device
     int num_cus;
     int waves_per_cu;  // caller's cap on resident wavefronts per compute unit used to size the grid; <= 0: family default
 };
@@ -124,8 +127,11 @@ __device__ __forceinline__ int vec_overlap(int col, int row_len) {
 // Lane `gl` of a group holds vectors gl, gl+G, gl+2G, ... of its row, so one load
 // instruction of a wavefront covers 64/G consecutive rows in 16*G-byte pieces.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, int G, int NV, int MK, int MODE>
-__global__ __launch_bounds__(64 * kWaveFamilyWaves) void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
+// WPE: most wavefronts per SIMD the kernel wants resident (8 = whatever its registers allow).  The compiler sizes
+// the kernel's register allocation so that no more fit; nothing else changes.
+template <typename T, int VEC, int G, int NV, int MK, int MODE, int WPE = 8>
+__global__ __launch_bounds__(64 * kWaveFamilyWaves) __attribute__((amdgpu_waves_per_eu(1, WPE)))
+void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
     constexpr bool MASK = MK == kMaskAdditive;
     constexpr bool VARLEN = MK == kMaskLengths;
     constexpr bool UA = MODE == kModeUnder;
@@ -559,14 +565,21 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
         }
     }
     // Element-aligned 4-byte rows stream best with few wavefronts resident (their accesses straddle cache lines, and the
-    // more of them are in flight the more they thrash): an LDS allocation that the kernel does not use holds a compute
-    // unit at 5 workgroups (20 wavefronts), at 4 for rows of 384 floats and more.  Measured on 77..1001 floats, with and
-    // without an additive mask: +1..4 points of HBM peak (config 2: 128.8 -> 123.2 us); 2-byte elements, which have half the
-    // bytes in flight per wavefront, lose with any such limit.
-    unsigned lds_limit = 0;
-    if constexpr (MODE == kModeUnder && sizeof(T) == 4 && MK != kMaskLengths) lds_limit = a.Sk >= 384 ? 40000 : 32000;
-    hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)),
-                       dim3(64 * kWaveFamilyWaves), lds_limit, s, a, n_tiles);
+    // more of them are in flight the more they thrash): the kernel is built to hold a SIMD at 5 wavefronts (20 per compute
+    // unit), at 4 for rows of 384 floats and more.  Measured on 77..1001 floats, with and without an additive mask:
+    // +1..4 points of HBM peak (config 2: 128.8 -> 123.2 us); 2-byte elements, which have half the bytes in flight per
+    // wavefront, lose with any such limit.  Rows of 384 floats and more have at least 2 vectors per lane on 64 lanes,
+    // shorter rows at most 2, so only that shape needs both builds.
+    const dim3 grid(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)), block(64 * kWaveFamilyWaves);
+    if constexpr (MODE == kModeUnder && sizeof(T) == 4 && MK != kMaskLengths) {
+        constexpr bool kShort = G < 64 || NV == 1, kLong = G == 64 && NV >= 3;
+        if (kShort || (!kLong && a.Sk < 384))
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
+        else
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
+    } else {
+        hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), grid, block, 0, s, a, n_tiles);
+    }
     return hipGetLastError();
 }
 

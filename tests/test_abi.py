@@ -11,7 +11,7 @@ import torch
 from paper_2010_05680_amd import binding as tb
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADERS = [os.path.join(ROOT, "include", h) for h in ("turbo_reduce.h", "turbo_serving.h")]
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("turbo_reduce.h", "turbo_reduce_testing.h", "turbo_serving.h")]
 
 FAKE = 0x10000  # a non-null, 16-byte aligned "device pointer"; validation must fail before it is used
 

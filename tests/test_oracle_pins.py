@@ -308,3 +308,18 @@ def test_oracle_threads_do_not_change_results():
     y4 = orc.masked_softmax(c.scores, c.mask, c.mask_stride_b, c.mask_stride_q, c.scale)
     orc.set_threads(1)
     np.testing.assert_array_equal(y1, y4)
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle is the reference everything else is judged by, so its own memory accesses are checked: every
+    function runs on exactly sized heap buffers in a build with -fsanitize=address,undefined (tests/native/oracle_sanitize.c)."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "oracle_sanitize"
+    subprocess.check_call(["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan",
+                           os.path.join(root, "tests", "native", "oracle_sanitize.c"), "-o", str(exe), "-lm"])
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300,
+                         env=dict(os.environ, ASAN_OPTIONS="detect_leaks=1"))
+    assert res.returncode == 0 and res.stdout.startswith("ok"), res.stdout + res.stderr
