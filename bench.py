@@ -52,8 +52,9 @@ def parse_args():
                          "of the two for kernels long enough to hide the host's launch cost")
     ap.add_argument("--kernel-iters", type=int, default=100, help="launches per kernel timing loop")
     ap.add_argument("--traffic-probe", type=int, default=0,
-                    help="run only: one plain copy of a known size, then N cold launches of each kernel of --config; "
-                         "meant to run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`")
+                    help="run only: one plain copy of a known size, then N cold launches of each kernel of --config and "
+                         "of the plain streams over the same buffers; meant to run under `rocprofv3 --pmc <counters>`")
+    ap.add_argument("--probe-warm", type=int, default=0, help="with --traffic-probe: 1 = reuse one buffer set (cache-resident)")
     return ap.parse_args()
 
 
@@ -194,23 +195,34 @@ def _time_launches(torch, stream, fn, iters, period, launch):
 COPY_PROBE_BYTES = 256 << 20
 
 
-def traffic_probe(torch, ks, stream, n):
-    """Calibration copy + n launches of each kernel, eager, on one stream, for HBM-byte counters.
+def traffic_probe(torch, tb, ks, stream, n, warm):
+    """Calibration copy, then n launches each of: the softmax, the LayerNorm, and the plain streams of the same bytes
+    and buffers (in-place copy, two-input add); eager, on one stream, for rocprofv3 counter runs.
 
     The copy is torch's elementwise copy kernel over COPY_PROBE_BYTES (reads that many bytes, writes that
-    many): the ratio counter/known-bytes it yields scales the counters of the two kernels."""
+    many): the ratio counter/known-bytes it yields scales the byte counters of the other kernels.  With `warm`
+    every launch uses buffer set 0 (what a cache-resident tensor costs); otherwise the sets rotate (cold)."""
     src = torch.randn(COPY_PROBE_BYTES // 4, device="cuda")
     dst = torch.empty_like(src)
+    pick = (lambda i: 0) if warm else (lambda i: i)
     with torch.cuda.stream(stream):
         for _ in range(3):
             dst.copy_(src)
         for i in range(n):
-            ks.softmax(i, stream)
+            ks.softmax(pick(i), stream)
         for i in range(n):
-            ks.layernorm(i, stream)
+            ks.layernorm(pick(i), stream)
+        for i in range(n):
+            t = ks.scores[pick(i) % ks.n_sm_sets]
+            tb.turbo_stream_probe(t, None, t, stream=stream)
+        for i in range(n):
+            j = pick(i) % ks.n_ln_sets
+            tb.turbo_stream_probe(ks.x[j], ks.res[j], ks.out[j], stream=stream)
         stream.synchronize()
-    print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": COPY_PROBE_BYTES,
-                      "softmax_bytes": ks.softmax_bytes, "layernorm_bytes": ks.layernorm_bytes, "launches": n}))
+    print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": COPY_PROBE_BYTES, "regime": "warm" if warm else "cold",
+                      "softmax_bytes": ks.softmax_bytes, "layernorm_bytes": ks.layernorm_bytes, "launches": n,
+                      "order": ["3 x calibration copy", "softmax", "layernorm", "stream_probe in place (softmax's bytes)",
+                                "stream_probe two inputs (LayerNorm's tensors)"]}))
 
 
 def elementwise_table(torch, tb, stream, launch, iters):
@@ -470,7 +482,7 @@ def main():
         spec = dataclasses.replace(spec, dtype=np.float32 if args.dtype == "f32" else np.float16)
     ks = KernelSets(spec, torch, tb, wl, seed=args.seed)
     if args.traffic_probe:
-        traffic_probe(torch, ks, stream, args.traffic_probe)
+        traffic_probe(torch, tb, ks, stream, args.traffic_probe, args.probe_warm)
         return
     period = max(ks.n_sm_sets, ks.n_ln_sets)
     step_bytes = ks.softmax_bytes + ks.layernorm_bytes

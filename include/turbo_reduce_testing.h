@@ -25,6 +25,8 @@ extern "C" {
  *                           narrow kernels instead of element-aligned 16-byte accesses for odd row lengths
  *   TURBO_OVR_GRID_WAVES    cap on resident workgroups (of 4 wavefronts) per compute unit used to size the grid
  *                           of the looping kernels
+ *   TURBO_OVR_GRID_BLOCKS   exact number of workgroups of the kernels that loop over tiles or rows (all softmax
+ *                           kernels, the workgroup-per-row and two-sweep LayerNorm), never more than there are tiles or rows
  *   TURBO_OVR_BLOCK_WAVES   wavefronts per row (2..16) of the block family, used when the row then fits the
  *                           registers of that many wavefronts and is accessed with 16-byte vectors; otherwise the
  *                           built-in choice stands
@@ -50,7 +52,7 @@ extern "C" {
  * Asynchronous on `stream`; allocates nothing.
  */
 enum turbo_override { TURBO_OVR_PATH = 0, TURBO_OVR_MAX_VEC_BYTES = 1, TURBO_OVR_GRID_WAVES = 2, TURBO_OVR_BLOCK_WAVES = 3,
-                      TURBO_OVR_COUNT_ = 4 };
+                      TURBO_OVR_GRID_BLOCKS = 4, TURBO_OVR_COUNT_ = 5 };
 int turbo_set_override(int key, int value);
 int turbo_describe_plan(int op, int rows, int row_len, int dtype, int aligned16, char *buf, int buf_len);
 unsigned turbo_debug_fastdiv(unsigned n, unsigned d);

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("TURBO_REDUCE_LIB") or os.path.join(_HERE, "libturbo_r
 
 TURBO_OK, TURBO_ERR_NULL, TURBO_ERR_SHAPE, TURBO_ERR_DTYPE, TURBO_ERR_ALIGN, TURBO_ERR_LAUNCH = range(6)
 TURBO_F32, TURBO_F16 = 0, 1
-TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES, TURBO_OVR_BLOCK_WAVES = 0, 1, 2, 3
+TURBO_OVR_PATH, TURBO_OVR_MAX_VEC_BYTES, TURBO_OVR_GRID_WAVES, TURBO_OVR_BLOCK_WAVES, TURBO_OVR_GRID_BLOCKS = 0, 1, 2, 3, 4
 PATH_WAVE, PATH_BLOCK, PATH_STREAM = 0, 1, 2
 
 EXPORTED_SYMBOLS = (

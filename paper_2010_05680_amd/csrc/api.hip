@@ -19,7 +19,7 @@ namespace {
 
 // Process-wide switches of the testing hooks (turbo_reduce_testing.h).  Relaxed atomics: a test flips them between
 // calls, never during one; the atomics only keep a concurrent reader free of a data race.
-std::atomic<int> g_ovr_value[TURBO_OVR_COUNT_] = {{-1}, {-1}, {-1}, {-1}};
+std::atomic<int> g_ovr_value[TURBO_OVR_COUNT_] = {{-1}, {-1}, {-1}, {-1}, {-1}};
 
 turbo::Overrides current_overrides() {
     turbo::Overrides o;
@@ -27,6 +27,7 @@ turbo::Overrides current_overrides() {
     o.max_vec_bytes = g_ovr_value[TURBO_OVR_MAX_VEC_BYTES].load(std::memory_order_relaxed);
     o.grid_waves = g_ovr_value[TURBO_OVR_GRID_WAVES].load(std::memory_order_relaxed);
     o.block_waves = g_ovr_value[TURBO_OVR_BLOCK_WAVES].load(std::memory_order_relaxed);
+    o.grid_blocks = g_ovr_value[TURBO_OVR_GRID_BLOCKS].load(std::memory_order_relaxed);
     return o;
 }
 
@@ -70,6 +71,7 @@ int current_device(turbo::LaunchCfg* lc) {
 
 int launch_cfg(const turbo::Overrides& ovr, turbo::LaunchCfg* lc) {
     if (int st = current_device(lc)) return st;
+    lc->grid_blocks = ovr.grid_blocks > 0 ? ovr.grid_blocks : 0;
     lc->waves_per_cu = ovr.grid_waves > 0 ? (ovr.grid_waves > (1 << 20) ? (1 << 22) : ovr.grid_waves * 4) : 0;
     return TURBO_OK;
 }

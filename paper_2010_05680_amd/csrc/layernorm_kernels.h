@@ -615,8 +615,8 @@ constexpr bool block_shape_compiled() {
 
 template <typename T, int VEC, int NV, bool RES, int MODE>
 hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    // The kernel loops over rows with a fixed assignment of rows to workgroups, so the grid is a whole number of
-    // "rounds" of what the chip holds at once: a partial last round would run with most compute units idle.
+    // The kernel loops over rows with a fixed assignment of rows to workgroups; the grid is a whole multiple of the
+    // compute-unit count and never more than the chip holds at once.
     // Workgroups of w wavefronts of THIS kernel that one compute unit of device d holds; 0 = not asked yet.  One table per
     // kernel instantiation, keyed by device and workgroup size.  Concurrent first calls store the same number, so
     // relaxed atomics suffice.
@@ -634,12 +634,20 @@ hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const L
         if (cached) resident[lc.device][p.waves].store(n, std::memory_order_relaxed);
     }
     int grid;
-    if (lc.waves_per_cu > 0) {
+    if (lc.grid_blocks > 0) {
+        grid = a.n_rows < lc.grid_blocks ? a.n_rows : lc.grid_blocks;
+    } else if (lc.waves_per_cu > 0) {
         grid = capped_grid(a.n_rows, p.waves, kLayerNormBlockCap, lc);
     } else {
-        // measured: small workgroups stream best with three rounds, workgroups of 5 or more wavefronts with one
-        const int rounds = p.waves <= 4 ? 3 : 1;
-        const long long cap = (long long)lc.num_cus * per_cu * rounds;
+        // Measured over workgroups of 2..16 wavefronts, 1..8 workgroups per compute unit, both element types, row counts
+        // that divide the grid and row counts that do not: the kernel streams best with the same number of workgroups on
+        // every compute unit (a grid of 683 or 820 instead of 768 loses 3-8 points of HBM peak) and about 8 wavefronts
+        // per compute unit, each looping over many rows -- 12 for workgroups of 2 or 3 wavefronts are no worse, and
+        // workgroups of 8 wavefronts whose lanes need bounds checks want two per compute unit.  [4096, 4096] fp32:
+        // 77.0 % of HBM peak with 256 workgroups of 16 rows each, 75.0 % with the 768 that fit the chip at once.
+        int per_cu_wanted = p.waves <= 3 ? 4 : p.waves <= 7 ? 2 : (p.waves == 8 && MODE != kModeFull) ? 2 : 1;
+        if (per_cu_wanted > per_cu) per_cu_wanted = per_cu;
+        const long long cap = (long long)lc.num_cus * per_cu_wanted;
         grid = (int)(a.n_rows < cap ? a.n_rows : cap);
     }
     hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>), dim3(grid), dim3(64 * p.waves), 0, s, a);

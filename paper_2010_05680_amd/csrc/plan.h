@@ -91,6 +91,7 @@ struct Overrides {
     int path = -1;
     int max_vec_bytes = -1;
     int grid_waves = -1;
+    int grid_blocks = -1;  // > 0: exact grid of the looping kernels
     int no_full = 0;    // 1: the call needs per-row bounds checks (per-request lengths), never the exact-tiling mode
     int no_stream = 0;  // 1: the call cannot use the two-sweep family
     int block_waves = -1;  // 2..16: wavefronts per row in the block family, when the row then fits the register budget

@@ -51,6 +51,7 @@ struct LaunchCfg {
     int device;    // the current HIP device
     int num_cus;
     int waves_per_cu;  // caller's cap on resident wavefronts per compute unit used to size the grid; <= 0: family default
+    int grid_blocks;   // > 0: exact grid of the looping kernels (testing hook), still capped by the work items
 };
 
 // Default grid caps, in wavefronts per compute unit (0 = one tile or row per workgroup, no cap).
@@ -537,7 +538,9 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
 inline int capped_grid(long long work_items, int waves_per_block, int default_cap, const LaunchCfg& lc) {
     const int cap_waves = lc.waves_per_cu > 0 ? lc.waves_per_cu : default_cap;
     long long g = work_items;
-    if (cap_waves > 0) {
+    if (lc.grid_blocks > 0) {  // every kernel sized here loops over its tiles or rows
+        if (g > lc.grid_blocks) g = lc.grid_blocks;
+    } else if (cap_waves > 0) {
         long long cap = (long long)lc.num_cus * cap_waves / waves_per_block;
         if (cap < lc.num_cus) cap = lc.num_cus;
         if (g > cap) g = cap;

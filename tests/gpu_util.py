@@ -16,15 +16,17 @@ def dev(a: np.ndarray) -> torch.Tensor:
 
 
 @contextlib.contextmanager
-def overrides(path=-1, max_vec_bytes=-1, grid_waves=-1, block_waves=-1):
+def overrides(path=-1, max_vec_bytes=-1, grid_waves=-1, block_waves=-1, grid_blocks=-1):
     tb.turbo_set_override(tb.TURBO_OVR_BLOCK_WAVES, block_waves)
+    tb.turbo_set_override(tb.TURBO_OVR_GRID_BLOCKS, grid_blocks)
     tb.turbo_set_override(tb.TURBO_OVR_PATH, path)
     tb.turbo_set_override(tb.TURBO_OVR_MAX_VEC_BYTES, max_vec_bytes)
     tb.turbo_set_override(tb.TURBO_OVR_GRID_WAVES, grid_waves)
     try:
         yield
     finally:
-        for k in (tb.TURBO_OVR_PATH, tb.TURBO_OVR_MAX_VEC_BYTES, tb.TURBO_OVR_GRID_WAVES, tb.TURBO_OVR_BLOCK_WAVES):
+        for k in (tb.TURBO_OVR_PATH, tb.TURBO_OVR_MAX_VEC_BYTES, tb.TURBO_OVR_GRID_WAVES, tb.TURBO_OVR_BLOCK_WAVES,
+                  tb.TURBO_OVR_GRID_BLOCKS):
             tb.turbo_set_override(k, -1)
 
 

@@ -101,6 +101,28 @@ def test_packed_softmax_is_the_padded_batch_without_its_padding():
     np.testing.assert_array_equal(y, _pack([y_pad[b, :, :n, :n] for b, n in enumerate(lens)]))
 
 
+def test_packed_softmax_with_one_request_longer_than_a_wavefront_can_hold():
+    """A request of 4500 keys beside short ones (rows of 4500 values need more than the 4096 binary32 values one
+    wavefront's registers hold, so the HIP path serves it with a workgroup per row): the library softmax per request,
+    a closed form, and the offsets of the requests behind the long one."""
+    rng = np.random.default_rng(5)
+    H, lens = 1, [3, 4500, 2]
+    blocks = [rng.normal(size=(H, n, n)) * 3 for n in lens]
+    # row 7 of the long request: a geometric progression, z_k = k ln(r) with r = 0.999: weights r^k (1 - r) / (1 - r^n)
+    n, r = 4500, 0.999
+    blocks[1][0, 7] = np.arange(n) * np.log(r) / 0.25
+    y = orc.masked_softmax_packed(_pack(blocks), lens, H, 0.25)
+    pos = 0
+    for m, blk in zip(lens, blocks):
+        want = torch.softmax(torch.from_numpy(blk) * 0.25, -1).numpy()
+        np.testing.assert_allclose(y[pos:pos + H * m * m].reshape(H, m, m), want, rtol=1e-12, atol=1e-300)
+        pos += H * m * m
+    assert pos == y.size
+    closed = r ** np.arange(n) * (1 - r) / (1 - r ** n)
+    np.testing.assert_allclose(y[9 + 7 * n:9 + 8 * n], closed, rtol=1e-11)
+    np.testing.assert_allclose(y[9:9 + n * n].reshape(n, n).sum(-1), 1.0, rtol=0, atol=1e-12)
+
+
 # ------------------------------------------------------------------ causal variant
 
 def test_causal_softmax_by_hand():
