@@ -126,7 +126,8 @@ int turbo_masked_softmax_causal(void *scores, const int *q_lengths, const int *k
  * total_tokens:  the caller's HOST copy of cu_seqlens[B] (sizes the launch);  max_len: HOST upper bound on len_b
  *                (sizes the registers per row); what happens to a request longer than max_len is unspecified (it is
  *                either computed like the others or left untouched; nothing outside it is touched).
- * At most one wavefront holds a row, so max_len is at most 4096 (TURBO_F32) or 8192 (TURBO_F16) (TURBO_ERR_SHAPE beyond).
+ * Requests of up to 4096 (TURBO_F32) or 8192 (TURBO_F16) tokens keep a row in one wavefront's registers; when max_len
+ * is larger, a second kernel launch gives every longer row a workgroup.  max_len is at most 32768 (TURBO_ERR_SHAPE beyond).
  * The LayerNorm of a packed batch needs no entry point of its own: its tokens are [total_tokens, hidden] rows of
  * turbo_add_bias_layernorm_dt.
  */

@@ -325,7 +325,7 @@ int turbo_masked_softmax_packed(void* scores, const int* cu_seqlens, const long 
     if (es == 0) return TURBO_ERR_DTYPE;
     if (B <= 0 || H <= 0 || total_tokens <= 0 || max_len <= 0 || max_len > total_tokens) return TURBO_ERR_SHAPE;
     if ((long long)H * total_tokens > kMaxRows) return TURBO_ERR_SHAPE;
-    if (max_len > 64 * 16 * (16 / es)) return TURBO_ERR_SHAPE;  // one wavefront holds a row: 16 vectors per lane at most
+    if (max_len > turbo::kPackedBlockMaxLen) return TURBO_ERR_SHAPE;  // a workgroup's registers hold a row
     if (reinterpret_cast<uintptr_t>(scores) % es != 0 || reinterpret_cast<uintptr_t>(cu_seqlens) % 4 != 0 ||
         reinterpret_cast<uintptr_t>(score_offsets) % 8 != 0)
         return TURBO_ERR_ALIGN;
@@ -337,6 +337,7 @@ int turbo_masked_softmax_packed(void* scores, const int* cu_seqlens, const long 
     a.H = H;
     a.n_rows = H * total_tokens;
     a.scale = scale;
+    a.long_from = 0;
     const turbo::Overrides ovr = current_overrides();
     turbo::LaunchCfg lc;
     if (int st = launch_cfg(ovr, &lc)) return st;

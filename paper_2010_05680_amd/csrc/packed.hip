@@ -54,15 +54,48 @@ hipError_t packed_tv(const PackedSoftmaxArgs& a, int max_len, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Rows beyond one wavefront's registers span more than 1024 vectors, so the workgroup is always the largest one (16
+// wavefronts) and max_len only decides the vectors per lane (2, 3, 4 or 8: at most 32 elements).
+template <typename T, int VEC>
+hipError_t packed_block_tv(const PackedSoftmaxArgs& a, int max_len, hipStream_t s) {
+    constexpr int waves = kBlockMaxWaves;
+    const int nvec = (max_len + VEC - 1) / VEC;
+    const int per_lane = (nvec + kWave * waves - 1) / (kWave * waves);
+    const int nv = per_lane <= 2 ? 2 : per_lane <= 3 ? 3 : per_lane <= 4 ? 4 : 8;
+    if ((long long)kWave * waves * nv * VEC < max_len || nv * VEC > 32) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)a.n_rows), block(kWave * waves);
+    switch (nv) {
+        case 2: hipLaunchKernelGGL((softmax_packed_block_kernel<T, VEC, 2>), grid, block, 0, s, a); break;
+        case 3: hipLaunchKernelGGL((softmax_packed_block_kernel<T, VEC, 3>), grid, block, 0, s, a); break;
+        case 4: hipLaunchKernelGGL((softmax_packed_block_kernel<T, VEC, 4>), grid, block, 0, s, a); break;
+        case 8:
+            if constexpr (8 * VEC <= 32) {
+                hipLaunchKernelGGL((softmax_packed_block_kernel<T, VEC, 8>), grid, block, 0, s, a);
+                break;
+            }
+            return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_softmax_packed(const PackedSoftmaxArgs& a, int elem_size, int max_len, int num_cus, int grid_cap_per_cu,
                                  bool rows_kernel, hipStream_t s) {
+    const int wave_max = elem_size == 4 ? packed_wave_max_len<float>() : packed_wave_max_len<_Float16>();
+    const int short_len = max_len < wave_max ? max_len : wave_max;  // what the wavefront-per-row kernels are sized for
+    hipError_t err;
     // the request-shaped kernel keeps the length table in the lanes of a wavefront: up to 63 requests
     if (a.B < kWave && !rows_kernel)
-        return elem_size == 4 ? packed_groups_tv<float, 4>(a, max_len, num_cus, grid_cap_per_cu, s)
-                              : packed_groups_tv<_Float16, 8>(a, max_len, num_cus, grid_cap_per_cu, s);
-    return elem_size == 4 ? packed_tv<float, 4>(a, max_len, s) : packed_tv<_Float16, 8>(a, max_len, s);
+        err = elem_size == 4 ? packed_groups_tv<float, 4>(a, short_len, num_cus, grid_cap_per_cu, s)
+                             : packed_groups_tv<_Float16, 8>(a, short_len, num_cus, grid_cap_per_cu, s);
+    else
+        err = elem_size == 4 ? packed_tv<float, 4>(a, short_len, s) : packed_tv<_Float16, 8>(a, short_len, s);
+    if (err != hipSuccess || max_len <= wave_max) return err;
+    // requests beyond a wavefront's registers: a second launch over the same batch, a workgroup per long row
+    PackedSoftmaxArgs b = a;
+    b.long_from = wave_max;
+    return elem_size == 4 ? packed_block_tv<float, 4>(b, max_len, s) : packed_block_tv<_Float16, 8>(b, max_len, s);
 }
 
 }  // namespace turbo

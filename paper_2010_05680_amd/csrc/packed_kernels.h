@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_utils.h"
+#include "softmax_kernels.h"  // SoftmaxLds, softmax_block_combine
 
 namespace turbo {
 
@@ -22,7 +23,15 @@ struct PackedSoftmaxArgs {
     int B, H;
     int n_rows;  // H * cu_seqlens[B]
     float scale;
+    int long_from;  // workgroup-per-row kernel: rows of at most this many elements are another kernel's and are skipped
 };
+
+// Longest row one wavefront holds in registers (16 vectors of 16 bytes per lane); longer rows take a workgroup.
+template <typename T>
+constexpr int packed_wave_max_len() {
+    return kWave * 16 * (16 / (int)sizeof(T));
+}
+constexpr int kPackedBlockMaxLen = 32768;  // 16 wavefronts x 64 lanes x 32 elements per lane, either element type
 
 constexpr int kPackedWaves = 4;  // wavefronts per workgroup
 
@@ -380,7 +389,88 @@ void softmax_packed_groups_kernel(PackedSoftmaxArgs a) {
     }
 }
 
-// max_len decides the register shape; returns hipErrorInvalidValue when a row of max_len does not fit a wavefront.
+// ---------------------------------------------------------------------------
+// Requests longer than one wavefront's registers: a workgroup of blockDim.x / 64 wavefronts per row, NV vectors per
+// lane, the per-wavefront (reference, sum) pairs combined through LDS with one barrier -- the padded block family's
+// scheme on a row whose length and start come from the request tables.  One row per workgroup (short-lived
+// workgroups stream best for the softmax).  Rows of at most `long_from` elements belong to the wavefront-per-row
+// kernels, which run over the same batch and in turn leave the long rows alone; those workgroups exit at once.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int NV>
+__global__ __launch_bounds__(1024) void softmax_packed_block_kernel(PackedSoftmaxArgs a) {
+    __shared__ SoftmaxLds lds;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int bd = (int)blockDim.x;
+    const int row = blockIdx.x;
+    if (row >= a.n_rows) return;
+
+    // request of this row: the largest b with H * cu_seqlens[b] <= row (the same for the whole workgroup)
+    int lo = 0, hi = a.B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((long long)a.H * a.cu_seqlens[mid] <= row)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    const int first = a.cu_seqlens[lo];
+    const int n = a.cu_seqlens[lo + 1] - first;
+    if (n <= a.long_from || n > bd * NV * VEC) return;  // another kernel's row, or longer than the caller's max_len
+    T* rp = reinterpret_cast<T*>(a.scores) + a.score_offsets[lo] + (long long)(row - a.H * first) * n;
+
+    float z[NV][VEC];
+    float m[1] = {-INFINITY};
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * bd + tid) * VEC;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) z[v][j] = -INFINITY;
+        if (c < n) {  // n >= VEC here: the last, partial vector is the one that ends at the row end
+            const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp + packed_vec_start<VEC>(c, n));
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                z[v][j] = (float)raw.v[j] * a.scale;
+                m[0] = fmaxf(m[0], z[v][j]);
+            }
+        }
+    }
+    group_allreduce<kWave, 1>(m, MaxOp{});
+    const float mu_w = m[0] * kLog2e;  // the wavefront's reference in the exponent domain, rounded once
+    const float shift = (mu_w == -INFINITY) ? 0.f : -mu_w;
+
+    float l[1] = {0.f};
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * bd + tid) * VEC;
+        const int dup = c < n ? c - packed_vec_start<VEC>(c, n) : 0;  // leading elements that the neighbour already counts
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const float e = fast_exp2(fmaf(z[v][j], kLog2e, shift));  // 0 where nothing was loaded (-inf)
+            z[v][j] = e;
+            l[0] += j >= dup ? e : 0.f;
+        }
+    }
+    group_allreduce<kWave, 1>(l, SumOp{});
+    const float f = softmax_block_combine(lds, 0, wave, lane, n_waves, mu_w, l[0]);
+
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * bd + tid) * VEC;
+        if (c < n) {  // the overlapped elements are written twice, with the same values
+            Pack<T, VEC> o;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) o.v[j] = (T)(z[v][j] * f);
+            store_stream<T, VEC, true>(rp + packed_vec_start<VEC>(c, n), o);
+        }
+    }
+}
+
+// max_len decides the register shape: up to one wavefront's capacity the request-shaped kernel (or, for 64 requests and
+// more, the wavefront-per-row kernel) does everything; beyond it that kernel serves the requests that fit a wavefront
+// and the workgroup-per-row kernel the longer ones.  Returns hipErrorInvalidValue beyond kPackedBlockMaxLen.
 // num_cus / grid_cap_per_cu (workgroups per compute unit, 0 = none) size the grid of the request-shaped kernel.
 hipError_t launch_softmax_packed(const PackedSoftmaxArgs& a, int elem_size, int max_len, int num_cus, int grid_cap_per_cu,
                                  bool rows_kernel, hipStream_t s);

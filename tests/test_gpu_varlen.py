@@ -229,6 +229,36 @@ def test_packed_softmax_shapes(dtype):
                 assert torch.isnan(buf[:lead]).all() and torch.isnan(buf[lead + total:]).all(), "wrote outside the batch"
 
 
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_packed_softmax_long_requests_take_a_workgroup_per_row(dtype):
+    """Requests beyond one wavefront's registers (4096 binary32 / 8192 binary16 values per row) are served by a second
+    launch over the same batch that gives every such row a workgroup; the shorter requests around them stay with the
+    wavefront kernels.  max_len sizes the registers of that workgroup, so larger bounds run the same rows through
+    every vectors-per-lane shape (2, 3, 4, 8)."""
+    rng = np.random.Generator(np.random.Philox(35))
+    wave_max = 4096 if dtype == F32 else 8192
+    lengths, H = [wave_max + (404 if dtype == F32 else 108), 3] + ([wave_max + 1] if dtype == F32 else []) + [0, 77], 1
+    lengths += [1100] * 23  # max_len may not exceed the token total: enough tokens for the largest bound
+    total = H * sum(n * n for n in lengths)
+    flat = (rng.standard_normal(total, dtype=np.float32) * 3).astype(dtype)
+    orc.set_threads(gu.host_threads())
+    want = orc.masked_softmax_packed(flat, lengths, H, 0.125)
+    orc.set_threads(1)
+    bounds = [max(lengths), 3 * 1024 * (4 if dtype == F32 else 8), 4 * 1024 * (4 if dtype == F32 else 8), 32768]
+    for i, max_len in enumerate(sorted(set(bounds))):
+        for mode in ({}, {"path": 0}) if i == 0 else ({},):
+            with gu.overrides(**mode):
+                got, buf = _run_packed(flat, lengths, H, 0.125, dtype, max_len=max_len, lead=3, tail=16)
+            assert_parity(got, want, dtype, f"packed softmax, long requests, max_len={max_len} {mode}")
+            assert torch.isnan(buf[:3]).all() and torch.isnan(buf[3 + total:]).all(), "wrote outside the batch"
+    # a bound below the longest request: that request is left alone (or computed), everything else is computed
+    got, _ = _run_packed(flat, lengths, H, 0.125, dtype, max_len=wave_max + 100, lead=0, tail=0)
+    _, off = wl.packed_layout(lengths, H)
+    assert_parity(got[off[1]:], want[off[1]:], dtype, "requests behind one that exceeds max_len")
+    first = got[:off[1]]
+    assert np.array_equal(first, flat[:off[1]]) or np.allclose(first, want[:off[1]], rtol=3e-3, atol=1e-6)
+
+
 def test_packed_softmax_max_len_is_an_upper_bound_and_longer_requests_are_left_alone():
     rng = np.random.Generator(np.random.Philox(32))
     lengths, H = [40, 300, 9], 2
@@ -278,8 +308,8 @@ def test_packed_error_paths():
     assert f(fake, None, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_NULL
     assert f(fake, fake, fake, 0, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE
     assert f(fake, fake, fake, 1, 1, 4, 5, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE     # max_len > total_tokens
-    assert f(fake, fake, fake, 1, 1, 5000, 4097, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # beyond one wavefront
-    assert f(fake, fake, fake, 1, 1, 9000, 8193, 1.0, tb.TURBO_F16, None) == tb.TURBO_ERR_SHAPE
+    assert f(fake, fake, fake, 1, 1, 40000, 32769, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_SHAPE  # beyond one workgroup
+    assert f(fake, fake, fake, 1, 1, 40000, 32769, 1.0, tb.TURBO_F16, None) == tb.TURBO_ERR_SHAPE
     assert f(fake, fake + 2, fake, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert f(fake, fake, fake + 4, 1, 1, 4, 4, 1.0, tb.TURBO_F32, None) == tb.TURBO_ERR_ALIGN
     assert f(fake, fake, fake, 1, 1, 4, 4, 1.0, 9, None) == tb.TURBO_ERR_DTYPE
