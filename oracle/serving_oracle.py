@@ -4,9 +4,11 @@
   exhaustive search: sort the requests by length, try every way of cutting the sorted list into consecutive
   batches of at most `max_batch` requests, keep the cheapest.  A batch of b requests whose longest has length L
   costs cached_cost[L][b] * b.
-* memory planning (Section 4.2, Algorithm 1): not a definition but a greedy heuristic, so the oracle takes the
-  algorithm's steps in the paper's order and notation (FindGapFromChunk, MemAllocate), in plain Python, plus a
-  checker of the property the plan must have: tensors whose life times overlap never share bytes.
+* memory planning (Section 4.2, Algorithm 1): a greedy heuristic whose result is not unique, so what is checked is
+  the contract a plan must meet -- tensors whose life times overlap never share bytes and stay inside their chunk,
+  a new chunk has max(default, ceil(k * size)) bytes, the footprint is bounded below by the peak of live bytes --
+  and, on instances of a few dozen bytes, the greedy choice itself by brute force over a byte map of every chunk
+  (largest tensor first, first chunk with room, tightest hole, a new chunk only when nothing has room).
 * cost table from samples (Section 6.3): bilinear weights over a sample grid, continued outside it.
 
 Pinned by tests/test_serving_host.py (hand cases, closed forms, invariants).  Shares nothing with the C++ code.
@@ -79,55 +81,95 @@ def cost_table_from_samples(sample_len: Sequence[int], sample_batch: Sequence[in
 
 # ---------------------------------------------------------------- memory planning (Algorithm 1)
 
-INVALID = None
+def _alive_together(first_op, last_op, a: int, b: int) -> bool:
+    return first_op[a] <= last_op[b] and first_op[b] <= last_op[a]
 
 
-def find_gap_from_chunk(t: int, chunk: List[Tuple[int, int]], chunk_size: int, first_op, last_op, size):
-    """chunk: records (tensor_id, offset) in increasing offset order.  Returns an offset or INVALID."""
-    smallest_gap = math.inf
-    prev_offset = 0
-    best_offset = INVALID
-    for x, offset_x in chunk:
-        max_first_op = max(first_op[t], first_op[x])
-        min_last_op = min(last_op[t], last_op[x])
-        if max_first_op <= min_last_op:
-            gap = offset_x - prev_offset
-            if gap >= size[t] and gap < smallest_gap:
-                smallest_gap = gap
-                best_offset = prev_offset
-            prev_offset = max(prev_offset, offset_x + size[x])
-    if best_offset is INVALID and chunk_size - prev_offset >= size[t]:
-        best_offset = prev_offset
-    return best_offset
+def greedy_plan_by_byte_map(first_op, last_op, size, held_chunks: Sequence[int], default_chunk_size: int,
+                            k_scale: float):
+    """The plan the greedy rule fixes, found by brute force on a byte map (only for instances of a few dozen bytes).
 
-
-def mem_allocate(first_op, last_op, size, chunk_sizes: Sequence[int], default_chunk_size: int = 2 << 20,
-                 k_scale: float = 1.2):
-    """Returns (assigned_chunk, assigned_offset, chunk sizes in use afterwards)."""
+    Tensors are taken largest first (equal sizes in input order).  For every chunk, in order, the bytes that some
+    tensor alive together with the new one occupies are marked in a list of booleans, and the maximal runs of free
+    bytes are read off it.  A run that ends at an occupied byte is a hole; the run that reaches the chunk's end is
+    the open room.  The first chunk with a hole or open room that is long enough takes the tensor: at the start of
+    the shortest sufficient hole (the lowest one among equals), else at the start of the open room.  If no chunk has
+    room a chunk of max(default, ceil(k * size)) bytes is added.  Chunks that end up empty are dropped and the rest
+    renumbered.  Returns (assigned_chunk, assigned_offset, chunk sizes in use)."""
     n = len(size)
-    order = sorted(range(n), key=lambda i: -size[i])  # non-increasing size, stable
-    sizes = list(chunk_sizes)
-    chunks: List[List[Tuple[int, int]]] = [[] for _ in sizes]
-    assigned_chunk = [None] * n
-    assigned_offset = [None] * n
+    order = sorted(range(n), key=lambda t: (-size[t], t))
+    capacities = [int(c) for c in held_chunks]
+    members: List[List[int]] = [[] for _ in capacities]
+    where = [None] * n  # (chunk, offset)
     for t in order:
-        is_assigned = False
-        for chunk_id, chunk in enumerate(chunks):
-            offset = find_gap_from_chunk(t, chunk, sizes[chunk_id], first_op, last_op, size)
-            if offset is not INVALID:
-                assigned_chunk[t], assigned_offset[t] = chunk_id, offset
-                chunk.append((t, offset))
-                chunk.sort(key=lambda r: r[1])
-                is_assigned = True
+        target = None
+        for c, cap in enumerate(capacities):
+            taken = [False] * cap
+            for r in members[c]:
+                if _alive_together(first_op, last_op, t, r):
+                    for byte in range(where[r][1], where[r][1] + size[r]):
+                        taken[byte] = True
+            runs = []  # (start, length, reaches_the_end)
+            byte = 0
+            while byte < cap:
+                if taken[byte]:
+                    byte += 1
+                    continue
+                begin = byte
+                while byte < cap and not taken[byte]:
+                    byte += 1
+                runs.append((begin, byte - begin, byte == cap))
+            holes = [(length, begin) for begin, length, open_end in runs if not open_end and length >= size[t]]
+            room = [begin for begin, length, open_end in runs if open_end and length >= size[t]]
+            if holes:
+                target = (c, min(holes)[1])
+            elif room:
+                target = (c, room[0])
+            if target is not None:
                 break
-        if not is_assigned:
-            new_chunk_size = max(default_chunk_size, math.ceil(size[t] * k_scale))
-            assigned_chunk[t], assigned_offset[t] = len(chunks), 0
-            sizes.append(new_chunk_size)
-            chunks.append([(t, 0)])
-    used = [c for c in range(len(chunks)) if chunks[c]]
-    renumber = {c: i for i, c in enumerate(used)}
-    return [renumber[c] for c in assigned_chunk], assigned_offset, [sizes[c] for c in used]
+        if target is None:
+            capacities.append(max(int(default_chunk_size), math.ceil(size[t] * k_scale)))
+            members.append([])
+            target = (len(capacities) - 1, 0)
+        members[target[0]].append(t)
+        where[t] = target
+    used = [c for c in range(len(capacities)) if members[c]]
+    new_index = {c: i for i, c in enumerate(used)}
+    return [new_index[where[t][0]] for t in range(n)], [where[t][1] for t in range(n)], [capacities[c] for c in used]
+
+
+def chunk_size_violations(size, assigned_chunk, assigned_offset, chunk_sizes, held_chunks: Sequence[int],
+                          default_chunk_size: int, k_scale: float) -> List[str]:
+    """The sizes of the chunks in use: the chunks kept from earlier inferences appear in their old order with their old
+    sizes (those that ended up empty are dropped), then the chunks opened by this plan, each of
+    max(default, ceil(k * size of the tensor that opened it)) bytes; that tensor sits at offset 0 and is the largest
+    of its chunk, because tensors are placed largest first."""
+    bad = []
+    held = list(held_chunks)
+    pos = 0
+    kept = 0
+    for c, cap in enumerate(chunk_sizes):
+        while pos < len(held) and held[pos] != cap:  # dropped chunks
+            pos += 1
+        if pos < len(held):
+            pos += 1
+            kept += 1
+            continue
+        # not one of the held chunks: must follow the size rule for its largest tensor, which starts at offset 0
+        inside = [t for t in range(len(size)) if assigned_chunk[t] == c]
+        if not inside:
+            bad.append(f"chunk {c} is in the list but holds no tensor")
+            continue
+        opener = max(inside, key=lambda t: size[t])
+        want = max(int(default_chunk_size), math.ceil(size[opener] * k_scale))
+        if cap != want:
+            bad.append(f"new chunk {c} has {cap} bytes, the rule gives {want}")
+        if not any(assigned_offset[t] == 0 and size[t] == size[opener] for t in inside):
+            bad.append(f"new chunk {c}: no largest tensor at offset 0")
+    for c in range(len(chunk_sizes)):
+        if not any(assigned_chunk[t] == c for t in range(len(size))):
+            bad.append(f"chunk {c} is kept although it holds no tensor")
+    return bad
 
 
 def plan_violations(first_op, last_op, size, assigned_chunk, assigned_offset, chunk_sizes) -> List[str]:

@@ -101,31 +101,49 @@ extern "C" int turbo_cost_table_fill(const int* sample_len, int n_len, const int
 
 namespace {
 
-struct Placed {
-    int tensor;
-    long long offset;
+// The planner's contract (Section 4.2): tensors whose life times overlap never share bytes; tensors are placed
+// largest first; a tensor goes into the first chunk that has room for it, into the tightest hole that holds it, and
+// a new chunk is opened only when no chunk has room.  The paper's Algorithm 1 is one way to meet it; what follows is
+// written from that contract: per chunk, the bytes that are busy while the tensor lives are swept once in address
+// order and the holes between them are the candidates.
+
+struct Span {  // bytes [begin, end) of a chunk
+    long long begin, end;
 };
 
-// Smallest gap of `chunk` that can hold tensor t among the tensors alive at the same time, or -1.
-long long find_gap(const std::vector<Placed>& chunk, long long chunk_size, int t, const int* first_op,
-                   const int* last_op, const long long* size) {
-    long long smallest_gap = std::numeric_limits<long long>::max();
-    long long prev_offset = 0;
-    long long best_offset = -1;
-    for (const Placed& x : chunk) {  // kept in increasing offset order
-        const int max_first = std::max(first_op[t], first_op[x.tensor]);
-        const int min_last = std::min(last_op[t], last_op[x.tensor]);
-        if (max_first <= min_last) {  // life times overlap
-            const long long gap = x.offset - prev_offset;
-            if (gap >= size[t] && gap < smallest_gap) {
-                smallest_gap = gap;
-                best_offset = prev_offset;
-            }
-            prev_offset = std::max(prev_offset, x.offset + size[x.tensor]);
+struct Chunk {
+    long long capacity;
+    std::vector<int> residents;  // tensors placed in this chunk so far, in no particular order
+};
+
+struct Lifetimes {
+    const int* first_op;
+    const int* last_op;
+    bool overlap(int a, int b) const { return first_op[a] <= last_op[b] && first_op[b] <= last_op[a]; }
+};
+
+// Offset for `need` bytes of tensor t in `chunk`, or -1 when the chunk has no room while t lives.
+// `busy` is scratch storage reused between calls.
+long long place_in_chunk(const Chunk& chunk, int t, long long need, const Lifetimes& life, const long long* size,
+                         const long long* offset_of, std::vector<Span>& busy) {
+    busy.clear();
+    for (int r : chunk.residents)
+        if (life.overlap(t, r)) busy.push_back(Span{offset_of[r], offset_of[r] + size[r]});
+    std::sort(busy.begin(), busy.end(), [](const Span& a, const Span& b) { return a.begin < b.begin; });
+
+    long long frontier = 0;    // everything below is covered by the spans seen so far, or is a hole already examined
+    long long tightest = -1;   // begin of the smallest hole that holds the tensor
+    long long tightest_len = std::numeric_limits<long long>::max();
+    for (const Span& sp : busy) {
+        const long long hole = sp.begin - frontier;  // <= 0 when the span starts inside covered bytes
+        if (hole >= need && hole < tightest_len) {
+            tightest = frontier;
+            tightest_len = hole;
         }
+        frontier = std::max(frontier, sp.end);
     }
-    if (best_offset < 0 && chunk_size - prev_offset >= size[t]) best_offset = prev_offset;
-    return best_offset;
+    if (tightest >= 0) return tightest;                       // a hole between residents is preferred ...
+    return chunk.capacity - frontier >= need ? frontier : -1;  // ... to the open room behind the last of them
 }
 
 }  // namespace
@@ -143,42 +161,42 @@ extern "C" int turbo_mem_plan(const int* first_op, const int* last_op, const lon
     for (int c = 0; c < *n_chunks; ++c)
         if (chunk_sizes[c] <= 0) return TURBO_ERR_SHAPE;
 
-    std::vector<int> by_size(n);
-    std::iota(by_size.begin(), by_size.end(), 0);
-    std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return size[a] > size[b]; });
+    // largest first; equal sizes keep their input order
+    std::vector<int> placement_order(n);
+    std::iota(placement_order.begin(), placement_order.end(), 0);
+    std::stable_sort(placement_order.begin(), placement_order.end(), [&](int a, int b) { return size[a] > size[b]; });
 
-    std::vector<long long> sizes(chunk_sizes, chunk_sizes + *n_chunks);
-    std::vector<std::vector<Placed>> chunks(sizes.size());
-    for (int t : by_size) {
-        bool assigned = false;
-        for (size_t c = 0; c < chunks.size() && !assigned; ++c) {
-            const long long off = find_gap(chunks[c], sizes[c], t, first_op, last_op, size);
-            if (off >= 0) {
-                assigned_chunk[t] = (int)c;
-                assigned_offset[t] = off;
-                auto pos = std::upper_bound(chunks[c].begin(), chunks[c].end(), off,
-                                            [](long long o, const Placed& p) { return o < p.offset; });
-                chunks[c].insert(pos, Placed{t, off});
-                assigned = true;
-            }
+    std::vector<Chunk> chunks(*n_chunks);
+    for (int c = 0; c < *n_chunks; ++c) chunks[c].capacity = chunk_sizes[c];  // kept from earlier inferences, empty
+    const Lifetimes life{first_op, last_op};
+    std::vector<Span> busy;
+    for (int t : placement_order) {
+        int home = -1;
+        long long at = -1;
+        for (size_t c = 0; c < chunks.size() && home < 0; ++c) {
+            at = place_in_chunk(chunks[c], t, size[t], life, size, assigned_offset, busy);
+            if (at >= 0) home = (int)c;
         }
-        if (!assigned) {
-            const long long scaled = (long long)std::ceil((double)size[t] * k_scale);
-            sizes.push_back(std::max(default_chunk_size, scaled));
-            chunks.push_back({Placed{t, 0}});
-            assigned_chunk[t] = (int)chunks.size() - 1;
-            assigned_offset[t] = 0;
+        if (home < 0) {  // nothing fits: a chunk of its own, with head room for somewhat longer requests
+            const long long with_head_room = (long long)std::ceil((double)size[t] * k_scale);
+            chunks.push_back(Chunk{std::max(default_chunk_size, with_head_room), {}});
+            home = (int)chunks.size() - 1;
+            at = 0;
         }
+        chunks[home].residents.push_back(t);
+        assigned_chunk[t] = home;
+        assigned_offset[t] = at;
     }
-    // release the chunks this inference does not use and renumber the rest
-    std::vector<int> new_index(chunks.size(), -1);
-    int kept = 0;
+
+    // chunks without a resident are given back; the others close ranks and the tensors follow
+    std::vector<int> renumbered(chunks.size(), -1);
+    int in_use = 0;
     for (size_t c = 0; c < chunks.size(); ++c)
-        if (!chunks[c].empty()) new_index[c] = kept++;
-    if (kept > max_chunks) return TURBO_ERR_SHAPE;
+        if (!chunks[c].residents.empty()) renumbered[c] = in_use++;
+    if (in_use > max_chunks) return TURBO_ERR_SHAPE;
     for (size_t c = 0; c < chunks.size(); ++c)
-        if (new_index[c] >= 0) chunk_sizes[new_index[c]] = sizes[c];
-    for (int t = 0; t < n; ++t) assigned_chunk[t] = new_index[assigned_chunk[t]];
-    *n_chunks = kept;
+        if (renumbered[c] >= 0) chunk_sizes[renumbered[c]] = chunks[c].capacity;
+    for (int t = 0; t < n; ++t) assigned_chunk[t] = renumbered[assigned_chunk[t]];
+    *n_chunks = in_use;
     return TURBO_OK;
 }

@@ -1,5 +1,6 @@
-"""Host-side planning routines (DP batch scheduler, sequence-length-aware allocator): the oracle against its pins,
-and the C++ implementation against the oracle, bit for bit.  CPU only."""
+"""Host-side planning routines (DP batch scheduler, sequence-length-aware allocator): the oracles against their pins,
+and the C++ implementation against them (the scheduler against exhaustive search; the allocator against its contract,
+hand cases and, on tiny instances, a byte-map brute force).  CPU only."""
 import math
 
 import numpy as np
@@ -172,45 +173,74 @@ def test_cost_table_feeds_the_scheduler_and_rejects_bad_grids():
     assert sv._lib().turbo_cost_table_fill(None, 1, None, 1, None, 1, 1, None) == tb.TURBO_ERR_NULL
 
 
-# ------------------------------------------------------------------ allocator: oracle pins
+# ------------------------------------------------------------------ allocator: hand cases and the contract
+#
+# A plan of this greedy heuristic is not unique in general, so there is no "expected output" to transcribe.  What is
+# fixed: the contract every plan must meet (so.plan_violations, so.chunk_size_violations, the peak of live bytes as a
+# lower bound), hand cases small enough to place by eye, and, on instances of a few dozen bytes, the greedy choice
+# itself, found by brute force on a byte map (so.greedy_plan_by_byte_map).  The hand cases pin the brute force too.
 
-def test_allocator_oracle_reuses_space_of_dead_tensors():
-    # two tensors that never live together share offset 0; a third that overlaps both goes behind the larger
+def _plans(first, last, size, held, default, k_scale=1.2):
+    """The C++ planner's plan and the byte-map brute force's, for cases small enough for the latter."""
+    return (sv.turbo_mem_plan(first, last, size, held, default, k_scale),
+            so.greedy_plan_by_byte_map(first, last, size, held, default, k_scale))
+
+
+def test_allocator_reuses_the_bytes_of_dead_tensors():
+    # two tensors that never live together share offset 0; a third that lives with both goes behind the larger
     first, last, size = [0, 3, 0], [2, 5, 5], [100, 80, 50]
-    chunk, offset, chunks = so.mem_allocate(first, last, size, [], default_chunk_size=256)
-    assert chunk == [0, 0, 0] and offset == [0, 0, 100] and chunks == [256]
-    assert so.plan_violations(first, last, size, chunk, offset, chunks) == []
+    for chunk, offset, chunks in _plans(first, last, size, [], 256):
+        assert chunk == [0, 0, 0] and offset == [0, 0, 100] and chunks == [256]
+        assert so.plan_violations(first, last, size, chunk, offset, chunks) == []
 
 
-def test_allocator_oracle_picks_the_smallest_sufficient_gap():
-    # A(100) B(30) C(60) alive over [0,9] packed at 0,100,130... then freed holes: place tensors so that two gaps
-    # of 40 and 25 exist between tensors alive with t; t (size 20) must take the 25-byte gap
-    first = [0, 0, 0, 0, 5]
-    last = [9, 9, 9, 9, 9]
-    size = [100, 40, 25, 60, 20]
-    # occupy offsets by hand through an existing layout: emulate with a chunk list and check find_gap directly
-    chunk = [(0, 0), (3, 140), (1, 225)]          # A@0..100, D@140..200, B@225..265 ; gaps: 40 (100..140), 25 (200..225)
-    got = so.find_gap_from_chunk(4, chunk, 400, first, last, size)
-    assert got == 200
-    assert so.find_gap_from_chunk(4, chunk, 400, first, last, [100, 40, 25, 60, 30]) == 100   # 30 only fits the 40-gap
-    assert so.find_gap_from_chunk(4, chunk, 400, first, last, [100, 40, 25, 60, 50]) == 265   # neither: after the last
-    assert so.find_gap_from_chunk(4, chunk, 300, first, last, [100, 40, 25, 60, 50]) is so.INVALID
-    # records that are dead while t lives do not count: with D dead, the gap is 100..225
-    first2, last2 = [0, 0, 0, 0, 5], [9, 9, 9, 3, 9]
-    assert so.find_gap_from_chunk(4, chunk, 400, first2, last2, [100, 40, 25, 60, 120]) == 100
+def test_allocator_takes_the_tightest_hole_that_holds_the_tensor():
+    """Placed largest first: A(100)@0, D(60)@100, X(45)@160, B(40)@205, Y(25)@245, Z(22)@270, all alive from the start.
+    X and Y die at operator 3, which leaves holes of 45 bytes at 160 and of 25 bytes at 245 for a tensor born at 5."""
+    first = [0, 0, 0, 0, 0, 0, 5]
+    last = [9, 9, 3, 9, 3, 9, 9]
+    base = [100, 60, 45, 40, 25, 22]
+    for newcomer, want_offset in ((20, 245),    # placed last; fits both holes: the 25-byte one is tighter
+                                  (25, 160),    # as large as Y, so placed before Z: behind B there is only open room
+                                  (30, 160)):   # placed before Y and Z; only the 45-byte hole holds it
+        size = base + [newcomer]
+        for chunk, offset, chunks in _plans(first, last, size, [], 400):
+            assert offset[:6] == [0, 100, 160, 205, 245, 270] and chunk == [0] * 7 and chunks == [400]
+            assert offset[6] == want_offset, (newcomer, offset)
+            assert so.plan_violations(first, last, size, chunk, offset, chunks) == []
+    # a newcomer of 50 bytes is placed third, behind D; X, which it never meets, then shares its first bytes, and
+    # everything smaller moves up: B behind the newcomer, Y behind B (the 5 bytes between X and B hold nothing), Z last
+    size = base + [50]
+    for chunk, offset, chunks in _plans(first, last, size, [], 400):
+        assert offset == [0, 100, 160, 210, 250, 275, 160] and chunks == [400]
+    # in a chunk of 280 bytes Z no longer fits behind Y: a second chunk of max(default, ceil(1.2 * 22)) bytes
+    for chunk, offset, chunks in _plans(first, last, size, [], 280):
+        assert chunk == [0, 0, 0, 0, 0, 1, 0] and offset[5] == 0 and chunks == [280, 280]
+    # a hole between two residents wins over open room behind them even when the open room is the tighter fit
+    first, last, size = [0, 0, 0, 4], [9, 2, 9, 9], [50, 30, 20, 10]
+    for chunk, offset, chunks in _plans(first, last, size, [], 112):
+        # A(50)@0, X(30)@50 dies at 2, Z(20)@80; the newcomer (10, born at 4) sees a hole of 30 at 50 and 12 bytes of
+        # open room at 100
+        assert offset == [0, 50, 80, 50] and chunks == [112]
 
 
-def test_allocator_oracle_new_chunks_and_release():
+def test_allocator_opens_chunks_by_the_size_rule_and_gives_back_unused_ones():
     first, last = [0, 0], [1, 1]
     # a tensor larger than the default chunk gets ceil(1.2 * size); the small one fits behind it
-    chunk, offset, chunks = so.mem_allocate(first, last, [1000, 10], [], default_chunk_size=512, k_scale=1.2)
-    assert chunks == [1200] and chunk == [0, 0] and offset == [0, 1000]
-    # chunks left over from a longer request are released when a short one does not need them
-    chunk, offset, chunks = so.mem_allocate([0], [0], [100], [512, 2048, 512], default_chunk_size=512)
-    assert chunks == [512] and chunk == [0]
+    for chunk, offset, chunks in _plans(first, last, [1000, 10], [], 512):
+        assert chunks == [1200] and chunk == [0, 0] and offset == [0, 1000]
+    # chunks left over from a longer request are given back when a short one does not need them
+    for chunk, offset, chunks in _plans([0], [0], [100], [512, 2048, 512], 512):
+        assert chunks == [512] and chunk == [0]
     # ... and the one that is used keeps its size even if it is not the first
-    chunk, offset, chunks = so.mem_allocate([0], [0], [1000], [512, 2048, 512], default_chunk_size=512)
-    assert chunks == [2048] and chunk == [0] and offset == [0]
+    for chunk, offset, chunks in _plans([0], [0], [1000], [512, 2048, 512], 512):
+        assert chunks == [2048] and chunk == [0] and offset == [0]
+    # the first chunk with room wins, not the one with the tightest hole
+    for chunk, offset, chunks in _plans([0], [0], [100], [2048, 128], 512):
+        assert chunks == [2048] and chunk == [0]
+    # ceil, not floor: 1.2 * 1001 = 1201.2
+    for chunk, offset, chunks in _plans([0], [0], [1001], [], 512):
+        assert chunks == [1202]
 
 
 def _bert_like_records(seq, rng=None):
@@ -224,27 +254,53 @@ def _bert_like_records(seq, rng=None):
 
 
 @pytest.mark.parametrize("seq", [5, 40, 128, 200, 240, 500])
-def test_allocator_oracle_plan_is_valid_and_not_wasteful(seq):
+def test_allocator_plan_is_valid_and_not_wasteful(seq):
     first, last, size = _bert_like_records(seq)
-    chunk, offset, chunks = so.mem_allocate(first, last, size, [])
+    chunk, offset, chunks = sv.turbo_mem_plan(first, last, size, [])
     assert so.plan_violations(first, last, size, chunk, offset, chunks) == []
+    assert so.chunk_size_violations(size, chunk, offset, chunks, [], 2 << 20, 1.2) == []
     peak = so.peak_live_bytes(first, last, size)
     assert sum(chunks) >= peak
     assert sum(chunks) <= max(2 << 20, 1.2 * peak) + len(chunks) * (2 << 20)
 
 
-def test_plan_checker_notices_a_bad_plan():
+def test_plan_checkers_notice_a_bad_plan():
     first, last, size = [0, 0], [1, 1], [10, 10]
     assert so.plan_violations(first, last, size, [0, 0], [0, 5], [100]) != []      # overlapping bytes
     assert so.plan_violations(first, last, size, [0, 0], [0, 95], [100]) != []     # leaves the chunk
     assert so.plan_violations(first, last, size, [0, 1], [0, 0], [100]) != []      # missing chunk
     assert so.plan_violations(first, last, size, [0, 0], [0, 10], [100]) == []
+    assert so.chunk_size_violations(size, [0, 0], [0, 10], [100], [], 100, 1.2) == []
+    assert so.chunk_size_violations(size, [0, 0], [0, 10], [101], [], 100, 1.2) != []    # not the rule's size
+    assert so.chunk_size_violations(size, [0, 0], [5, 15], [100], [], 100, 1.2) != []    # nothing at offset 0
+    assert so.chunk_size_violations(size, [0, 0], [0, 10], [100, 64], [64], 100, 1.2) != []  # an empty chunk is kept
+    assert so.peak_live_bytes([0, 2, 1], [1, 3, 2], [10, 20, 5]) == 25
 
 
-# ------------------------------------------------------------------ allocator: C++ against the oracle
+# ------------------------------------------------------------------ allocator: C++ against brute force and contract
+
+@pytest.mark.parametrize("seed", range(40))
+def test_allocator_makes_the_greedy_choice_on_instances_small_enough_for_brute_force(seed):
+    """A few tensors of a few bytes each: the byte-map brute force fixes the plan of the greedy rule, and the C++
+    planner must produce exactly it (equal sizes, holes of equal length and exact fits occur often at this scale)."""
+    rng = np.random.default_rng(300 + seed)
+    n = int(rng.integers(1, 14))
+    n_ops = int(rng.integers(1, 9))
+    first = [int(v) for v in rng.integers(0, n_ops, size=n)]
+    last = [min(n_ops - 1, f + int(d)) for f, d in zip(first, rng.integers(0, 4, size=n))]
+    size = [int(v) for v in rng.integers(1, 13, size=n)]
+    held = [int(v) for v in rng.integers(4, 40, size=int(rng.integers(0, 4)))]
+    default = int(rng.choice([8, 16, 48]))
+    k_scale = float(rng.choice([1.0, 1.2, 2.0]))
+    got = sv.turbo_mem_plan(first, last, size, held, default, k_scale)
+    want = so.greedy_plan_by_byte_map(first, last, size, held, default, k_scale)
+    assert got == want, (first, last, size, held, default, k_scale)
+    assert so.plan_violations(first, last, size, *got) == []
+    assert so.chunk_size_violations(size, *got, held, default, k_scale) == []
+
 
 @pytest.mark.parametrize("seed", range(20))
-def test_allocator_matches_oracle_bit_for_bit(seed):
+def test_allocator_meets_its_contract_on_large_random_instances(seed):
     rng = np.random.default_rng(100 + seed)
     n = int(rng.integers(1, 40))
     n_ops = int(rng.integers(1, 25))
@@ -253,26 +309,31 @@ def test_allocator_matches_oracle_bit_for_bit(seed):
     size = rng.integers(1, 5000, size=n) * int(rng.choice([1, 64, 1024]))
     held = [int(v) for v in rng.integers(1, 4, size=int(rng.integers(0, 4))) * 4096]
     default = int(rng.choice([1024, 4096, 2 << 20]))
-    got = sv.turbo_mem_plan(first, last, size, held, default, 1.2)
-    want = so.mem_allocate(list(first), list(last), [int(s) for s in size], held, default, 1.2)
-    assert got == (want[0], want[1], want[2])
-    assert so.plan_violations(first, last, size, *got) == []
+    chunk, offset, chunks = sv.turbo_mem_plan(first, last, size, held, default, 1.2)
+    assert so.plan_violations(first, last, size, chunk, offset, chunks) == []
+    assert so.chunk_size_violations([int(v) for v in size], chunk, offset, chunks, held, default, 1.2) == []
+    assert sum(chunks) >= so.peak_live_bytes(first, last, size)
+    # largest first: nothing larger than a chunk's resident at offset 0 can sit in a chunk this plan opened
+    assert len(chunks) <= len(held) + n
 
 
 @pytest.mark.parametrize("seqs", [[200, 240], [500, 5, 128], [40, 40, 41]])
 def test_allocator_across_consecutive_requests(seqs):
     """Chunks carry over from one inference to the next, as in the paper's Figure 6 scenario (length 200 then 240)."""
-    held_cpp, held_py = [], []
+    held = []
+    counts = []
     for seq in seqs:
         first, last, size = _bert_like_records(seq)
-        c1, o1, held_cpp = sv.turbo_mem_plan(first, last, size, held_cpp)
-        c2, o2, held_py = so.mem_allocate(first, last, size, held_py)
-        assert (c1, o1, held_cpp) == (c2, o2, held_py)
-        assert so.plan_violations(first, last, size, c1, o1, held_cpp) == []
+        before = list(held)
+        chunk, offset, held = sv.turbo_mem_plan(first, last, size, held)
+        assert so.plan_violations(first, last, size, chunk, offset, held) == []
+        assert so.chunk_size_violations(size, chunk, offset, held, before, 2 << 20, 1.2) == []
+        assert sum(held) >= so.peak_live_bytes(first, last, size)
+        counts.append(len(held))
     if seqs == [200, 240]:
-        first, last, size = _bert_like_records(200)
-        _, _, chunks200 = so.mem_allocate(first, last, size, [])
-        assert len(held_cpp) >= len(chunks200)  # the longer request keeps the chunks and may add to them
+        assert counts[1] >= counts[0]  # the longer request keeps the chunks and may add to them
+    if seqs == [40, 40, 41]:
+        assert counts[0] == counts[1]  # the same request again needs nothing new
 
 
 @pytest.mark.parametrize("seq", [17, 128, 493])
