@@ -346,16 +346,26 @@ __device__ __forceinline__ void layernorm_block_combine(LayerNormLds& lds, int s
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
 // Rotated like the wave family: the next row's loads are issued before this
 // row's barrier and stores.
-template <typename T, int VEC, int NV, bool RES, int MODE>
-__global__ __launch_bounds__(1024) void layernorm_block_kernel(LayerNormArgs a) {
+// Whether a workgroup of up to 16 wavefronts (128 registers per lane) can keep bias/gamma/beta in registers beside the
+// current and the prefetched row.  16-byte vectors of 2-byte elements hold their prefetched row in half the registers:
+// they fit like the mode without bounds checks does.
+template <typename T, int VEC, int NV, int MODE>
+constexpr bool block_params_fit_128() {
+    return NV * VEC <= ((sizeof(T) == 2 && VEC == 8)
+                            ? (MODE == kModeFull ? kBlockParamPreloadHalfElems : kBlockParamPreloadFullElems)
+                            : MODE == kModeFull ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
+}
+
+// ROOMY: the kernel is built for workgroups of at most 8 wavefronts, which leaves every lane up to 256 registers, and
+// keeps the parameters in registers whatever the shape; used for the shapes whose parameters do not fit 128 registers
+// (they would be re-read from the vector cache for every row: three more vector loads per slot and row on the path the
+// streams need) whenever the row is served by 8 wavefronts or fewer.
+template <typename T, int VEC, int NV, bool RES, int MODE, bool ROOMY = false>
+__global__ __launch_bounds__(ROOMY ? 512 : 1024) void layernorm_block_kernel(LayerNormArgs a) {
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     __shared__ LayerNormLds lds;
-    // 16-byte vectors of 2-byte elements hold their prefetched row in half the registers: they fit like the mode
-    // without bounds checks does
-    constexpr bool PRELOAD = NV * VEC <= ((sizeof(T) == 2 && VEC == 8)
-                                              ? (FULL ? kBlockParamPreloadHalfElems : kBlockParamPreloadFullElems)
-                                              : FULL ? kBlockParamPreloadFullElems : kBlockParamPreloadElems);
+    constexpr bool PRELOAD = ROOMY || block_params_fit_128<T, VEC, NV, MODE>();
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
@@ -613,8 +623,8 @@ constexpr bool block_shape_compiled() {
            (VEC * (int)sizeof(T) >= 16 || NV <= kLayerNormLimits.block_max_nv_narrow);
 }
 
-template <typename T, int VEC, int NV, bool RES, int MODE>
-hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+template <typename T, int VEC, int NV, bool RES, int MODE, bool ROOMY>
+hipError_t launch_layernorm_block_r(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
     // The kernel loops over rows with a fixed assignment of rows to workgroups; the grid is a whole multiple of the
     // compute-unit count and never more than the chip holds at once.
     // Workgroups of w wavefronts of THIS kernel that one compute unit of device d holds; 0 = not asked yet.  One table per
@@ -625,7 +635,7 @@ hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const L
     int per_cu = cached ? resident[lc.device][p.waves].load(std::memory_order_relaxed) : 0;
     if (per_cu == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, layernorm_block_kernel<T, VEC, NV, RES, MODE>, 64 * p.waves, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, layernorm_block_kernel<T, VEC, NV, RES, MODE, ROOMY>, 64 * p.waves, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = 16 / p.waves;
@@ -650,8 +660,16 @@ hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const L
         const long long cap = (long long)lc.num_cus * per_cu_wanted;
         grid = (int)(a.n_rows < cap ? a.n_rows : cap);
     }
-    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE>), dim3(grid), dim3(64 * p.waves), 0, s, a);
+    hipLaunchKernelGGL((layernorm_block_kernel<T, VEC, NV, RES, MODE, ROOMY>), dim3(grid), dim3(64 * p.waves), 0, s, a);
     return hipGetLastError();
+}
+
+template <typename T, int VEC, int NV, bool RES, int MODE>
+hipError_t launch_layernorm_block(const Plan& p, const LayerNormArgs& a, const LaunchCfg& lc, hipStream_t s) {
+    if constexpr (!block_params_fit_128<T, VEC, NV, MODE>()) {
+        if (p.waves <= 8) return launch_layernorm_block_r<T, VEC, NV, RES, MODE, true>(p, a, lc, s);
+    }
+    return launch_layernorm_block_r<T, VEC, NV, RES, MODE, false>(p, a, lc, s);
 }
 
 template <typename T, int VEC, bool RES, int MODE>
