@@ -575,11 +575,15 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
     // shorter rows at most 2, so only that shape needs both builds.
     const dim3 grid(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)), block(64 * kWaveFamilyWaves);
     if constexpr (MODE == kModeUnder && sizeof(T) == 4 && MK != kMaskLengths) {
-        constexpr bool kShort = G < 64 || NV == 1, kLong = G == 64 && NV >= 3;
-        if (kShort || (!kLong && a.Sk < 384))
+        if constexpr (G < 64 || NV == 1) {
             hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
-        else
+        } else if constexpr (NV >= 3) {
             hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
+        } else if (a.Sk < 384) {
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
+        } else {
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
+        }
     } else {
         hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), grid, block, 0, s, a, n_tiles);
     }
