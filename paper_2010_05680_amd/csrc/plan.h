@@ -69,7 +69,7 @@ struct OpLimits {
 #define TURBO_SM_BLOCK_FROM_BYTES 4096
 #endif
 #ifndef TURBO_LN_BLOCK_FROM_BYTES
-#define TURBO_LN_BLOCK_FROM_BYTES 5124  // rows of more than 1280 floats (6 vectors per lane in the wave family): +2-3 points
+#define TURBO_LN_BLOCK_FROM_BYTES 4608  // rows of 1152 floats and more (5 vectors per lane in the wave family): +3 points
 #endif
 constexpr OpLimits kSoftmaxLimits{TURBO_SM_TARGET_ELEMS, 64, TURBO_SM_BLOCK_PREF_NV, 32, TURBO_SM_BLOCK_FROM_BYTES, 16, 32, 12, 14, TURBO_SM_TARGET_ELEMS_UNDER, 0};
 constexpr OpLimits kLayerNormLimits{TURBO_LN_TARGET_ELEMS, 24, TURBO_LN_BLOCK_PREF_NV, 16, TURBO_LN_BLOCK_FROM_BYTES, 6, 24, 0, 0, TURBO_LN_TARGET_ELEMS, 1};
@@ -190,8 +190,7 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
         for (int nv = 3; nv >= 2 && !block_ok; --nv) {
             if (nvec % (64 * nv) != 0 || !block_fits(nv)) continue;
             const long long w = nvec / (64 * nv);
-            // 5..7 wavefronts x 2 vectors gain 1-8 points for 2-byte elements and lose 2 for 4-byte ones
-            if (nv == 2 && w >= 5 && w <= 7 && elem_size != 2) continue;
+            // (5..7 wavefronts x 2 vectors: 1-8 points over the next power of two for 2-byte elements, 2-3 for 4-byte ones)
             if (w >= 2 && w <= 8) {
                 block_ok = true;
                 block_w = (int)w;
@@ -220,6 +219,14 @@ inline Plan make_plan(int row_len, int elem_size, long long align_elems, long lo
     // 4-8 points faster there (softmax), and no slower for the LayerNorm.
     if (block_ok && block_w == 8 && block_nv == 2 && nvec <= 704 && vec * elem_size >= 16 && block_fits(3)) {
         block_w = 4;
+        block_nv = 3;
+    }
+    // Rows of 257..384 vectors: 2 wavefronts x 3 vectors cover the same 384 slots as 3 x 2 with one wavefront less at the
+    // barrier; measured equal for 4-byte elements and 1.5-3 points faster for 2-byte ones (LayerNorm only: its budget
+    // holds 3 vectors per lane, and the softmax reaches such rows in its wave family).
+    if (lim.block_exact_first && block_ok && block_w == 3 && block_nv == 2 && vec * elem_size >= 16 && block_fits(3) &&
+        nvec % (64 * 3 * 2) != 0) {
+        block_w = 2;
         block_nv = 3;
     }
     // (16-byte vectors only: with narrower ones not every count of vectors per lane is compiled)

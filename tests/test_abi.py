@@ -147,9 +147,15 @@ def test_plan_families_follow_row_length():
     assert P(1, 1000, 5120, tb.TURBO_F16).startswith("block vec=8f waves=5 nv=2")
     assert P(1, 1000, 6144, tb.TURBO_F16).startswith("block vec=8f waves=4 nv=3")
     assert P(1, 1000, 7168, tb.TURBO_F16).startswith("block vec=8f waves=7 nv=2")
-    assert P(1, 1000, 2560, tb.TURBO_F32).startswith("block vec=4 waves=4 nv=3")  # not 5 x 2 for 4-byte elements
+    assert P(1, 1000, 2560, tb.TURBO_F32).startswith("block vec=4f waves=5 nv=2")
+    # rows of 1152 floats and more leave the wave family; 257..384 vectors take 2 wavefronts x 3 vectors, not 3 x 2
+    assert P(1, 1000, 1024, tb.TURBO_F32).startswith("wave vec=4f lanes=64 nv=4")
+    assert P(1, 1000, 1152, tb.TURBO_F32).startswith("block vec=4 waves=2 nv=3")
+    assert P(1, 1000, 1280, tb.TURBO_F32).startswith("block vec=4 waves=2 nv=3")
+    assert P(1, 1000, 2304, tb.TURBO_F16).startswith("block vec=8 waves=2 nv=3")
+    assert P(1, 1000, 1280, tb.TURBO_F16).startswith("wave vec=8 lanes=64 nv=3")
     assert P(1, 1000, 2304, tb.TURBO_F32).startswith("block vec=4f waves=3 nv=3")
-    assert P(1, 1000, 2560, tb.TURBO_F16).startswith("block vec=8 waves=3 nv=2")  # three wavefronts, bounds-checked
+    assert P(1, 1000, 2560, tb.TURBO_F16).startswith("block vec=8 waves=2 nv=3")  # two wavefronts x 3, bounds-checked
     assert P(0, 1000, 4608, tb.TURBO_F16).startswith("block vec=8 waves=4 nv=3")  # 576 vectors: 4 x 3, not 8 x 2
     assert P(0, 1000, 6144, tb.TURBO_F16).startswith("block vec=8 waves=8 nv=2")
     tb.turbo_set_override(tb.TURBO_OVR_BLOCK_WAVES, 6)
@@ -203,7 +209,7 @@ def test_planner_invariants_over_many_shapes():
                             w, nv = kv["waves"], kv["nv"]
                             assert nv in supported_nv, what
                             # 5..7 wavefronts only where they tile the row exactly (LayerNorm)
-                            assert w in (2, 3, 4, 8, 16) or (op == 1 and mode == "f" and w in (5, 6, 7) and (nv == 3 or (nv == 2 and es == 2))), what
+                            assert w in (2, 3, 4, 8, 16) or (op == 1 and mode == "f" and w in (5, 6, 7) and nv in (2, 3)), what
                             budget = block_max_2byte if (es == 2 and vec == 8) else block_max
                             assert 64 * w * nv >= nvec and (nv * vec <= budget or nv == 1), what
                             if vec * es < 16 and op == 1:
