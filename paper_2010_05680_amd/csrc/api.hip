@@ -252,6 +252,7 @@ int permute_impl(const void* x, const void* bias, int B, int N1, int K, int N2, 
     // evenly, and a bias is only supported when it does not depend on that dimension (input order)
     const int unrolled = out_order ? N2 : N1;
     a.grouped = unrolled % turbo::kElemUnroll == 0 && !(bias != nullptr && out_order) && ovr.path != 2;
+    a.tiled = ovr.path < 0;  // testing hook: any forced family selects the kernels without LDS
     a.div_n1u = turbo::make_fastdiv((unsigned)(N1 % turbo::kElemUnroll == 0 ? N1 / turbo::kElemUnroll : 1));
     a.div_n2u = turbo::make_fastdiv((unsigned)(N2 % turbo::kElemUnroll == 0 ? N2 / turbo::kElemUnroll : 1));
     hipError_t err = turbo::launch_permute_heads(a, es, vec, reinterpret_cast<hipStream_t>(stream));

@@ -62,8 +62,73 @@ hipError_t gelu_tv(const GeluArgs& a0, bool ua, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Items (D elements) of at most this many bytes go through the LDS-tiled kernel: 256 where the input is the side with
+// the short runs (the head split; binary16 Q/K/V split of [64,512,3,H,D]: D = 16 23 -> 69 % of HBM peak, D = 32
+// 63 -> 74-77 %, D = 64 76 -> 79 %, and [8,4096,3,32,64] 63 -> 75 %; binary32 D = 64 on that shape 67 -> 76 %), 32 where
+// the output is (the head merge, whose strided 1 KiB reads do not stream as well as the split's strided writes:
+// D = 16 binary16 48 -> 58 %, but D = 32 70 -> 64 %, whatever the tile shape or the number of resident wavefronts).
+#ifndef TURBO_PERMUTE_TILED_MAX_ITEM_BYTES
+#define TURBO_PERMUTE_TILED_MAX_ITEM_BYTES 256
+#endif
+#ifndef TURBO_PERMUTE_TILED_MAX_ITEM_BYTES_MERGE
+#define TURBO_PERMUTE_TILED_MAX_ITEM_BYTES_MERGE 32
+#endif
+
+int log2_floor(int v) {
+    int l = 0;
+    while ((2 << l) <= v) ++l;
+    return l;
+}
+
+// The tiled kernel needs whole 16-byte vectors, a power-of-two number of them per item, and a tile count that fits
+// the grid; returns false when the shape is not for it.
+template <typename T, int VEC>
+bool launch_permute_tiled(const PermuteArgs& a, hipStream_t s, hipError_t* err) {
+  if constexpr (VEC * (int)sizeof(T) != 16) {
+    return false;
+  } else {
+    if (!a.tiled) return false;
+    const int dv = a.D / VEC;
+    const int item_bytes = a.D * (int)sizeof(T);
+    const int max_item = a.out_order ? TURBO_PERMUTE_TILED_MAX_ITEM_BYTES_MERGE : TURBO_PERMUTE_TILED_MAX_ITEM_BYTES;
+    if (dv < 1 || (dv & (dv - 1)) != 0 || item_bytes > max_item) return false;
+    // runs of up to 1 KiB on both sides, 16 KiB of items per tile; a short dimension hands its share to the other
+    int t_log2 = log2_floor(1024 / item_bytes);
+    int t2_log2 = t_log2, t1_log2 = t_log2;
+    auto ceil_log2 = [](int n) { int l = 0; while ((1 << l) < n) ++l; return l; };
+    if (ceil_log2(a.N2) < t2_log2) { t1_log2 += t2_log2 - ceil_log2(a.N2); t2_log2 = ceil_log2(a.N2); }
+    if (ceil_log2(a.N1) < t1_log2) { const int spare = t1_log2 - ceil_log2(a.N1); t1_log2 -= spare; t2_log2 += spare; }
+    if (ceil_log2(a.N2) < t2_log2) t2_log2 = ceil_log2(a.N2);
+    PermuteTileArgs t;
+    t.x = a.x; t.bias = a.bias; t.out = a.out;
+    t.B = a.B; t.N1 = a.N1; t.K = a.K; t.N2 = a.N2; t.D = a.D;
+    t.t1_log2 = t1_log2; t.t2_log2 = t2_log2; t.dv_log2 = log2_floor(dv);
+    const int row_vecs = dv << t2_log2;
+    t.row_stride = row_vecs + ((dv - row_vecs) % 16 + 16) % 16;  // congruent to dv modulo 16 vectors
+    t.tiles1 = (a.N1 + (1 << t1_log2) - 1) >> t1_log2;
+    t.tiles2 = (a.N2 + (1 << t2_log2) - 1) >> t2_log2;
+    const long long n_tiles = (long long)a.K * a.B * t.tiles1 * t.tiles2;
+    if (n_tiles > 0x7FFFFFFFll) return false;
+    t.div_tiles2 = make_fastdiv((unsigned)t.tiles2);
+    t.div_tiles1 = make_fastdiv((unsigned)t.tiles1);
+    t.div_b = make_fastdiv((unsigned)a.B);
+    const size_t lds = (size_t)t.row_stride * 16 * ((size_t)1 << t1_log2);
+    const dim3 grid((unsigned)n_tiles), block(kElemThreads);
+    if (a.bias)
+        hipLaunchKernelGGL((permute_heads_tiled_kernel<T, VEC, true>), grid, block, lds, s, t);
+    else
+        hipLaunchKernelGGL((permute_heads_tiled_kernel<T, VEC, false>), grid, block, lds, s, t);
+    *err = hipGetLastError();
+    return true;
+  }
+}
+
 template <typename T, int VEC>
 hipError_t permute_tv(const PermuteArgs& a, hipStream_t s) {
+    {
+        hipError_t err = hipSuccess;
+        if (launch_permute_tiled<T, VEC>(a, s, &err)) return err;
+    }
     if (a.grouped) {
         const long long items = a.total / (VEC * kElemUnroll);
         const dim3 g((unsigned)((items + kElemThreads - 1) / kElemThreads)), blk(kElemThreads);

@@ -4,7 +4,8 @@
 //
 // All three are pure streams (every element read once, written once), so the design is the one that reached the
 // copy ceiling in the reduction kernels: 16-byte non-temporal accesses, one short-lived workgroup per tile of
-// kElemUnroll * 256 vectors, all of a lane's loads issued before the first use.
+// kElemUnroll * 256 vectors, all of a lane's loads issued before the first use.  The head permutations of small
+// heads go through an LDS tile instead, so that both sides of the copy move in long runs.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -191,6 +192,7 @@ struct PermuteArgs {
     FastDiv div_dv, div_n2, div_k, div_n1, div_b;  // D/VEC, N2, K, N1, B
     FastDiv div_n1u, div_n2u;                      // N1/kElemUnroll, N2/kElemUnroll (grouped kernel)
     int grouped;  // 1: use the grouped kernel (the unrolled dimension divides evenly)
+    int tiled;    // 1: use the LDS-tiled kernel where the shape allows it (0: testing hook, never)
     int out_order;  // 1: lanes walk the output tensor, 0: the input tensor
 };
 
@@ -322,6 +324,84 @@ void permute_heads_grouped_kernel(PermuteArgs a) {
             for (int j = 0; j < VEC; ++j) o.v[j] = (T)((float)raw[u].v[j] + (float)pb.v[j]);
         }
         store_stream<T, VEC, false>(out + dst0 + u * dst_step, o);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Small heads (pieces of D elements that are shorter than 128 bytes): the kernels above keep one side of the copy
+// coalesced and move the other in pieces of D (or 4 D) elements, which for D = 32 binary16 values is 64 bytes and
+// costs 15-25 points of HBM peak.  Per (b, k) the permutation is the transpose of an N1 x N2 matrix of D-element
+// items, so a workgroup takes a tile of T1 x T2 items through LDS: it reads T1 runs of T2 items (contiguous in the
+// input), writes T2 runs of T1 items (contiguous in the output), both with 16-byte accesses in runs of up to 1 KiB.
+// LDS rows are padded so that the transposed read is free of bank conflicts: with DV vectors per item and a row
+// stride of (T2 * DV + pad) vectors, pad chosen so that the stride is congruent to DV modulo 16 vectors (256 bytes,
+// all 64 banks), 16 consecutive lanes of the read (DV vectors of 16 / DV consecutive rows) hit 16 different
+// 16-byte bank groups.
+// ---------------------------------------------------------------------------
+struct PermuteTileArgs {
+    const void* x;
+    const void* bias;  // may be null; [K][N2][D]
+    void* out;
+    int B, N1, K, N2, D;
+    int t1_log2, t2_log2, dv_log2;  // tile extents in items and vectors per item, all powers of two
+    int row_stride;                 // LDS row stride in vectors: T2 * DV + pad
+    int tiles1, tiles2;             // ceil(N1 / T1), ceil(N2 / T2)
+    FastDiv div_tiles2, div_tiles1, div_b;
+};
+
+template <typename T, int VEC, bool BIAS>
+__global__ __launch_bounds__(kElemThreads) void permute_heads_tiled_kernel(PermuteTileArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_raw[];
+    using V = Pack<T, VEC>;
+    V* tile = reinterpret_cast<V*>(tile_raw);
+    const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+    const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
+    T* out = reinterpret_cast<T*>(a.out);
+
+    // blockIdx.x = ((k * B + b) * tiles1 + tile1) * tiles2 + tile2
+    unsigned rest = blockIdx.x;
+    unsigned q = fastdiv(rest, a.div_tiles2);
+    const int n2_0 = (int)(rest - q * a.div_tiles2.d) << a.t2_log2;
+    rest = q;
+    q = fastdiv(rest, a.div_tiles1);
+    const int n1_0 = (int)(rest - q * a.div_tiles1.d) << a.t1_log2;
+    rest = q;
+    q = fastdiv(rest, a.div_b);
+    const int b = (int)(rest - q * a.div_b.d);
+    const int k = (int)q;
+
+    const int dv_mask = (1 << a.dv_log2) - 1;
+    const int n_slots = 1 << (a.t1_log2 + a.t2_log2 + a.dv_log2);
+    const long long in_base = (((long long)b * a.N1 + n1_0) * a.K + k) * a.N2 * a.D + (long long)n2_0 * a.D;
+    const long long in_row = (long long)a.K * a.N2 * a.D;  // one step of n1 in the input
+    const long long out_base = ((((long long)k * a.B + b) * a.N2 + n2_0) * a.N1 + n1_0) * a.D;
+    const long long out_row = (long long)a.N1 * a.D;       // one step of n2 in the output
+
+    // read: slot i = (n1l * T2 + n2l) * DV + dv, lanes run along the input's contiguous (n2, d)
+    for (int i = threadIdx.x; i < n_slots; i += kElemThreads) {
+        const int dv = i & dv_mask;
+        const int n2l = (i >> a.dv_log2) & ((1 << a.t2_log2) - 1);
+        const int n1l = i >> (a.dv_log2 + a.t2_log2);
+        if (n1_0 + n1l < a.N1 && n2_0 + n2l < a.N2) {
+            V v = load_stream<T, VEC, false>(x + in_base + n1l * in_row + (long long)n2l * a.D + dv * VEC);
+            if constexpr (BIAS) {
+                const V pb = load_pack<T, VEC, false>(bias + ((long long)k * a.N2 + n2_0 + n2l) * a.D + dv * VEC);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) v.v[j] = (T)((float)v.v[j] + (float)pb.v[j]);
+            }
+            tile[n1l * a.row_stride + (n2l << a.dv_log2) + dv] = v;
+        }
+    }
+    __syncthreads();
+    // write: slot i = (n2l * T1 + n1l) * DV + dv, lanes run along the output's contiguous (n1, d)
+    for (int i = threadIdx.x; i < n_slots; i += kElemThreads) {
+        const int dv = i & dv_mask;
+        const int n1l = (i >> a.dv_log2) & ((1 << a.t1_log2) - 1);
+        const int n2l = i >> (a.dv_log2 + a.t1_log2);
+        if (n1_0 + n1l < a.N1 && n2_0 + n2l < a.N2) {
+            const V v = tile[n1l * a.row_stride + (n2l << a.dv_log2) + dv];
+            store_stream<T, VEC, false>(out + out_base + n2l * out_row + (long long)n1l * a.D + dv * VEC, v);
+        }
     }
 }
 

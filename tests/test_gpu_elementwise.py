@@ -103,16 +103,21 @@ def test_gelu_unaligned_pointers_and_guard_bands(dtype):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16])
-def test_split_and_merge_heads(dtype):
+@pytest.mark.parametrize("path", [-1, 0, 2], ids=["planned", "no-lds", "flat"])
+def test_split_and_merge_heads(dtype, path):
+    """planned: small heads go through the LDS-tiled kernel (whole and partial tiles, one dimension shorter than a tile,
+    with and without bias); no-lds / flat: the two kernels without LDS on the same shapes."""
     rng = np.random.Generator(np.random.Philox(14))
     tdt = torch.float32 if dtype == F32 else torch.float16
     for B, S, K, H, D in [(1, 1, 1, 1, 1), (2, 5, 3, 4, 64), (20, 128, 3, 12, 64), (3, 17, 1, 5, 20), (2, 9, 2, 3, 6),
-                          (2, 7, 3, 2, 5), (1, 300, 3, 16, 64)]:
+                          (2, 7, 3, 2, 5), (1, 300, 3, 16, 64), (2, 37, 3, 5, 32), (1, 70, 2, 33, 16), (3, 33, 1, 7, 8),
+                          (2, 19, 3, 3, 128), (1, 5, 1, 70, 8), (2, 64, 3, 16, 32), (1, 129, 1, 2, 4), (1, 2, 2, 130, 16)]:
         x = _rand(rng, (B, S, K, H, D), dtype)
         bias = _rand(rng, (K, H, D), dtype, 0.3)
         for use_bias in (True, False):
             out = torch.full((K, B, H, S, D), float("nan"), dtype=tdt, device="cuda")
-            tb.turbo_add_bias_split_heads(gu.dev(x), gu.dev(bias) if use_bias else None, out)
+            with gu.overrides(path=path):
+                tb.turbo_add_bias_split_heads(gu.dev(x), gu.dev(bias) if use_bias else None, out)
             torch.cuda.synchronize()
             want = orc.add_bias_split_heads(x, bias if use_bias else None)
             if use_bias:
@@ -121,7 +126,8 @@ def test_split_and_merge_heads(dtype):
                 np.testing.assert_array_equal(_np(out).astype(np.float64), want)  # a pure permutation is bit-exact
         y = _rand(rng, (B, H, S, D), dtype)
         out = torch.full((B, S, H, D), float("nan"), dtype=tdt, device="cuda")
-        tb.turbo_merge_heads(gu.dev(y), out)
+        with gu.overrides(path=path):
+            tb.turbo_merge_heads(gu.dev(y), out)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(_np(out).astype(np.float64), orc.merge_heads(y))
 
@@ -221,8 +227,8 @@ def test_randomized_elementwise_cases(chunk):
         else:
             B, S, H = int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 9))
             D = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16, 20, 32, 64, 80]))
-            flat = bool(rng.random() < 0.3)
-            with gu.overrides(max_vec_bytes=cap, path=2 if flat else -1):
+            flat = int(rng.choice([-1, -1, 0, 2]))  # planned (LDS-tiled where the shape allows), no LDS, flat
+            with gu.overrides(max_vec_bytes=cap, path=flat):
                 if kind == "split":
                     K = int(rng.choice([1, 2, 3]))
                     x5, bias = _rand(rng, (B, S, K, H, D), dtype), _rand(rng, (K, H, D), dtype, 0.3)
