@@ -107,29 +107,37 @@ __global__ __launch_bounds__(64 * kPackedWaves) void softmax_packed_kernel(Packe
         rp[r] = reinterpret_cast<T*>(a.scores) + base + (long long)(row - a.H * first) * n;
     }
 
-    // len[r] is the same in every lane, so "this vector slot lies wholly beyond the row" is a scalar branch: short
-    // rows skip the slots they do not use instead of issuing their (empty) loads.
+    // All loads of a row are issued together and before the first use (a load under a per-slot branch would be followed by
+    // its own wait); slots beyond the row re-read its first vector and are masked afterwards.  len[r] is the same in
+    // every lane, so the branches below are scalar.
     float z[R][NV][VEC];
+    Pack<T, VEC> raw[R][NV];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (len[r] >= VEC) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int c = (v * kWave + lane) * VEC;
+                // the lane that owns the row's last, partial vector reads the vector that ends at the row end instead
+                // (it overlaps the neighbour's by VEC - len % VEC elements, which this lane leaves out of the sum)
+                raw[r][v] = load_stream<T, VEC, true>(rp[r] + (c < len[r] ? packed_vec_start<VEC>(c, len[r]) : 0));
+            }
+        }
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int c = (v * kWave + lane) * VEC;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) z[r][v][j] = -INFINITY;
-            if (v * kWave * VEC >= len[r]) continue;
             if (len[r] >= VEC) {
-                // the lane that owns the row's last, partial vector reads the vector that ends at the row end instead
-                // (it overlaps the neighbour's by VEC - len % VEC elements, which this lane leaves out of the sum)
-                if (c < len[r]) {
-                    const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, len[r]));
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * a.scale;
+                for (int j = 0; j < VEC; ++j) z[r][v][j] = c < len[r] ? (float)raw[r][v].v[j] * a.scale : -INFINITY;
+            } else {  // a row shorter than one vector: element by element, one lane
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    z[r][v][j] = -INFINITY;
+                    if (c == 0 && j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * a.scale;
                 }
-            } else if (c == 0) {  // a row shorter than one vector: element by element, one lane
-#pragma unroll
-                for (int j = 0; j < VEC; ++j)
-                    if (j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * a.scale;
             }
         }
 
@@ -234,27 +242,38 @@ __device__ __forceinline__ void packed_task(T* base, int n, int row0, int rows_b
         rp[r] = base + (long long)(row < rows_b ? row : 0) * n;
     }
 
+    // All loads of the task are issued before the first use, unconditionally: a load under a per-slot branch would be
+    // followed by its own wait, which leaves a wavefront one load in flight at a time.  Slots beyond the row (and
+    // rows beyond the request) re-read the start of a valid row and are masked afterwards.
     float z[R][NV][VEC];
+    if (n >= VEC) {
+        Pack<T, VEC> raw[R][NV];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int c = (v * G + gl) * VEC;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) z[r][v][j] = -INFINITY;
-            if (v * G * VEC >= n) continue;  // same in every lane: a scalar branch
-            if (n >= VEC) {
-                if (c < len[r]) {
-                    const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp[r] + packed_vec_start<VEC>(c, n));
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) z[r][v][j] = (float)raw.v[j] * scale;
-                }
-            } else if (gl == 0) {  // rows shorter than one vector: element by element, one lane per row
-#pragma unroll
-                for (int j = 0; j < VEC; ++j)
-                    if (j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * scale;
+            for (int v = 0; v < NV; ++v) {
+                const int c = (v * G + gl) * VEC;
+                raw[r][v] = load_stream<T, VEC, true>(rp[r] + (c < n ? packed_vec_start<VEC>(c, n) : 0));
             }
-        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const bool live = (v * G + gl) * VEC < len[r];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) z[r][v][j] = live ? (float)raw[r][v].v[j] * scale : -INFINITY;
+            }
+    } else {  // rows shorter than one vector: element by element, one lane per row
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    z[r][v][j] = -INFINITY;
+                    if (v == 0 && gl == 0 && j < len[r]) z[r][v][j] = (float)__builtin_nontemporal_load(rp[r] + j) * scale;
+                }
+    }
 
     float m[R];
 #pragma unroll
@@ -421,20 +440,23 @@ __global__ __launch_bounds__(1024) void softmax_packed_block_kernel(PackedSoftma
     if (n <= a.long_from || n > bd * NV * VEC) return;  // another kernel's row, or longer than the caller's max_len
     T* rp = reinterpret_cast<T*>(a.scores) + a.score_offsets[lo] + (long long)(row - a.H * first) * n;
 
+    // every load before the first use; slots beyond the row re-read its first vector and are masked (n >= VEC here, and
+    // the last, partial vector is the one that ends at the row end)
+    Pack<T, VEC> raw[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * bd + tid) * VEC;
+        raw[v] = load_stream<T, VEC, true>(rp + (c < n ? packed_vec_start<VEC>(c, n) : 0));
+    }
     float z[NV][VEC];
     float m[1] = {-INFINITY};
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-        const int c = (v * bd + tid) * VEC;
+        const bool live = (v * bd + tid) * VEC < n;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) z[v][j] = -INFINITY;
-        if (c < n) {  // n >= VEC here: the last, partial vector is the one that ends at the row end
-            const Pack<T, VEC> raw = load_stream<T, VEC, true>(rp + packed_vec_start<VEC>(c, n));
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                z[v][j] = (float)raw.v[j] * a.scale;
-                m[0] = fmaxf(m[0], z[v][j]);
-            }
+        for (int j = 0; j < VEC; ++j) {
+            z[v][j] = live ? (float)raw[v].v[j] * a.scale : -INFINITY;
+            m[0] = fmaxf(m[0], z[v][j]);
         }
     }
     group_allreduce<kWave, 1>(m, MaxOp{});
