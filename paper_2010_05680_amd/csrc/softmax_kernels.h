@@ -142,6 +142,16 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
     constexpr int GPW = kWave / G;  // lane groups per wavefront
     constexpr int kWaves = kWaveFamilyWaves;
     constexpr int TILE_ROWS = R * GPW * kWaves;
+    // Element-aligned rows of 2-byte elements with an additive mask: when the mask does not depend on the query (a
+    // per-request key mask) and the workgroup's rows belong to one request, one lane group fetches the mask row and hands
+    // it to the others through LDS in register layout, so the element-aligned mask loads -- the expensive operand, it
+    // comes through the vector cache, and at an odd element offset it is not even 4-byte aligned -- are issued once per
+    // workgroup instead of once per wavefront.  Measured against the same build without it (binary16, [B,Sk] mask):
+    // 197 / 333 / 777 / 1001 keys +2.7 / +1.8 / +3.3 / +1.5 points of HBM peak, 778 keys +3.6; rows whose two rows in
+    // flight already share their mask and whose mask rows are 4-byte aligned lose 0.5-4 points to the barrier (198, 334,
+    // 494 keys), as do 4-byte elements (-0.4..-2.9), so those keep the per-wavefront loads.
+    constexpr bool LDS_MASK = MASK && UA && sizeof(T) == 2;
+    __shared__ Pack<T, VEC> mask_lds[LDS_MASK ? NV * G : 1];
 
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int lane = threadIdx.x & (kWave - 1);
@@ -220,6 +230,14 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
             share_mask = a.mask_stride_q == 0 && first < a.n_rows &&
                          fastdiv((unsigned)first, a.div_rows_per_batch) == fastdiv((unsigned)last, a.div_rows_per_batch);
         }
+        bool wg_share = false;  // the same for every lane of the workgroup
+        if constexpr (LDS_MASK) {
+            const int first = tile * TILE_ROWS;
+            int last = first + TILE_ROWS - 1;
+            last = last < a.n_rows ? last : a.n_rows - 1;
+            wg_share = a.mask_stride_q == 0 && (R == 1 || (a.mask_stride_b & 1) != 0) &&
+                       fastdiv((unsigned)first, a.div_rows_per_batch) == fastdiv((unsigned)last, a.div_rows_per_batch);
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             int row = row_base + r * GPW;
@@ -238,11 +256,33 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
                     raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
                 }
                 if constexpr (MASK) {
-                    if (UA && R > 1 && r > 0 && share_mask)
+                    if (LDS_MASK && wg_share) {
+                        // lane group 0 of wavefront 0 fetches the row's mask for everyone (below, after all score loads)
+                    } else if (UA && R > 1 && r > 0 && share_mask) {
                         mraw[r][v] = mraw[0][v];
-                    else
+                    } else {
                         mraw[r][v] = load_pack<T, VEC, UA>(mp + colc);
+                    }
                 }
+            }
+        }
+        if constexpr (LDS_MASK) {
+            if (wg_share) {
+                if (wave == 0 && grp == 0) {
+                    const int rowc = tile * TILE_ROWS < a.n_rows ? tile * TILE_ROWS : a.n_rows - 1;
+                    const T* mp = mask_row_ptr<T, MASK>(a, rowc);
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+                        mask_lds[v * G + gl] = load_pack<T, VEC, UA>(mp + vec_start<VEC, UA>((v * G + gl) * VEC, Sk));
+                }
+                __syncthreads();
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const Pack<T, VEC> mv = mask_lds[v * G + gl];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) mraw[r][v] = mv;
+                }
+                __syncthreads();  // the next tile of a looping grid overwrites the LDS copy
             }
         }
 
