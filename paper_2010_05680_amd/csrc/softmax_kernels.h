@@ -23,9 +23,11 @@ namespace turbo {
 //   kMaskAdditive : an additive mask tensor is added to the scaled scores
 //   kMaskLengths  : per-request lengths: keys k >= k_len[b] get weight exactly 0 without being read, and rows
 //                   q >= q_len[b] are skipped altogether (the variable-length batches of Section 2.1, without
-//                   the cost of their zero padding); optionally causal: keys beyond the query's diagonal are
-//                   treated the same way
-enum MaskKind { kMaskNone = 0, kMaskAdditive = 1, kMaskLengths = 2 };
+//                   the cost of their zero padding)
+//   kMaskCausal   : the same, and query q also sees only the keys k <= q + (Sk - Sq); a build of its own because
+//                   every row then ends elsewhere, which changes what the lanes past a row's end should read
+enum MaskKind { kMaskNone = 0, kMaskAdditive = 1, kMaskLengths = 2, kMaskCausal = 3 };
+constexpr bool mask_by_lengths(int mask_kind) { return mask_kind >= kMaskLengths; }
 
 struct SoftmaxArgs {
     void* scores;
@@ -34,7 +36,7 @@ struct SoftmaxArgs {
     long long mask_stride_q;
     const int* k_lengths;  // kMaskLengths: [B] valid keys per request, or null = all Sk keys
     const int* q_lengths;  // kMaskLengths: [B] valid query rows per request, or null = all rows
-    int causal;            // kMaskLengths: 1 = query q also sees only the keys k <= q + (Sk - Sq)
+    int causal;            // 1 = the launcher takes the kMaskCausal build (the kernels do not read this)
     int n_rows;      // B*H*Sq
     int Sq;
     int Sk;
@@ -67,7 +69,7 @@ constexpr int kStreamCap = 32;
 // Elements of the rows in flight per lane in the wave family: fewer for element-aligned accesses, except with
 // per-request lengths, where half of a lane's vectors are typically not loaded at all.
 constexpr int softmax_wave_target_elems(int mask_kind, int mode, int row_elems_per_lane) {
-    if (mode != kModeUnder || mask_kind == kMaskLengths) return kSoftmaxLimits.target_elems;
+    if (mode != kModeUnder || mask_by_lengths(mask_kind)) return kSoftmaxLimits.target_elems;
     // with an additive mask two rows in flight let a per-request key mask be read once for both
     if (mask_kind == kMaskAdditive && row_elems_per_lane == kSoftmaxLimits.target_elems_under) return 2 * row_elems_per_lane;
     return kSoftmaxLimits.target_elems_under;
@@ -78,14 +80,15 @@ constexpr int rows_in_flight_c(int nv, int vec, int target) {
     return r >= 8 ? 8 : r >= 4 ? 4 : r >= 2 ? 2 : 1;
 }
 
-// kMaskLengths: number of valid keys of `row` (clamped to 0..Sk); 0 also for rows that are skipped.
+// kMaskLengths / kMaskCausal: number of valid keys of `row` (clamped to 0..Sk); 0 also for rows that are skipped.
+template <bool CAUSAL>
 __device__ __forceinline__ int row_key_count(const SoftmaxArgs& a, int row) {
     const unsigned b = fastdiv((unsigned)row, a.div_rows_per_batch);
     int klen = a.k_lengths != nullptr ? a.k_lengths[b] : a.Sk;
     klen = klen < 0 ? 0 : (klen > a.Sk ? a.Sk : klen);
-    if (a.q_lengths != nullptr || a.causal) {
+    if (CAUSAL || a.q_lengths != nullptr) {
         const int q = (int)((unsigned)row - fastdiv((unsigned)row, a.div_sq) * (unsigned)a.Sq);
-        if (a.causal) {
+        if constexpr (CAUSAL) {
             const int visible = q + (a.Sk - a.Sq) + 1;  // may be <= 0 when there are more queries than keys
             klen = visible < klen ? (visible < 0 ? 0 : visible) : klen;
         }
@@ -117,6 +120,15 @@ __device__ __forceinline__ int vec_start(int col, int row_len) {
     if constexpr (UA) return col + VEC <= row_len ? col : row_len - VEC;
     return col;
 }
+// Address that the lanes of a length-aware kernel read when their vector holds no valid key (they are not masked off:
+// loads under a branch are waited for one by one).  Any address inside the tensor will do, the data is discarded; one
+// per workgroup, 512 bytes apart, spreads these reads over the L2 channels where a single fixed address would send
+// every wavefront of the grid to the same one.
+template <typename T, int VEC>
+__device__ __forceinline__ const T* skipped_vector_address(const T* tensor, long long n_elems) {
+    const long long off = (long long)(blockIdx.x & 255) * (512 / (int)sizeof(T));
+    return off + VEC <= n_elems ? tensor + off : tensor;
+}
 template <int VEC, bool UA>
 __device__ __forceinline__ int vec_overlap(int col, int row_len) {
     if constexpr (UA) return (col < row_len && col + VEC > row_len) ? col + VEC - row_len : 0;
@@ -134,7 +146,8 @@ template <typename T, int VEC, int G, int NV, int MK, int MODE, int WPE = 8>
 __global__ __launch_bounds__(64 * kWaveFamilyWaves) __attribute__((amdgpu_waves_per_eu(1, WPE)))
 void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
     constexpr bool MASK = MK == kMaskAdditive;
-    constexpr bool VARLEN = MK == kMaskLengths;
+    constexpr bool VARLEN = mask_by_lengths(MK);
+    constexpr bool CAUSAL = MK == kMaskCausal;
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     static_assert(!(VARLEN && FULL), "per-row key counts need the bounds checks");
@@ -160,6 +173,8 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
     const int grp = lane / G;
     const int Sk = a.Sk;
     const float scale = a.scale;
+    const T* skip_addr = scores;  // what lanes without a valid key read
+    if constexpr (VARLEN) skip_addr = skipped_vector_address<T, VEC>(scores, (long long)a.n_rows * Sk);
 
     // Compact mode (per-request lengths, up to 63 requests): the padding rows q >= q_len[b] of a zero-padded batch
     // can be most of the tensor, and tiles made of them alone would still cost a workgroup launch each, or, with a
@@ -214,7 +229,7 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 int row = row_base + r * GPW;
-                klen[r] = row < row_limit ? row_key_count(a, row) : 0;
+                klen[r] = row < row_limit ? row_key_count<CAUSAL>(a, row) : 0;
                 any_row = any_row || klen[r] > 0;
             }
             if (__ballot(any_row) == 0) continue;  // a wavefront whose rows are all padding issues no memory traffic
@@ -249,9 +264,16 @@ void softmax_wave_kernel(SoftmaxArgs a, int n_tiles) {
             for (int v = 0; v < NV; ++v) {
                 int colc = FULL ? (v * G + gl) * VEC : vec_start<VEC, UA>((v * G + gl) * VEC, Sk);
                 if constexpr (VARLEN) {
-                    // vectors that hold no valid key are not fetched: they re-read the first bytes of the tensor
                     const bool needed = (v * G + gl) * VEC < Sk && colc < klen[r];
-                    raw[r][v] = load_stream<T, VEC, UA>(needed ? rp + colc : scores);
+                    if constexpr (CAUSAL) {
+                        // every row ends elsewhere: repeat the address of the row's last valid vector, which joins
+                        // the neighbouring lane's request and touches no further cache line (2-byte elements: +3..5 %
+                        // over skip_addr; with per-request key counts alone it measured 1..11 % slower than skip_addr)
+                        const int last = klen[r] > 0 ? vec_start<VEC, UA>((klen[r] - 1) / VEC * VEC, Sk) : 0;
+                        raw[r][v] = load_stream<T, VEC, UA>(rp + (needed ? colc : last));
+                    } else {
+                        raw[r][v] = load_stream<T, VEC, UA>(needed ? rp + colc : skip_addr);
+                    }
                 } else {
                     raw[r][v] = load_stream<T, VEC, UA>(rp + colc);
                 }
@@ -389,7 +411,8 @@ __device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot
 template <typename T, int VEC, int NV, int MK, int MODE>
 __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
     constexpr bool MASK = MK == kMaskAdditive;
-    constexpr bool VARLEN = MK == kMaskLengths;
+    constexpr bool VARLEN = mask_by_lengths(MK);
+    constexpr bool CAUSAL = MK == kMaskCausal;
     constexpr bool UA = MODE == kModeUnder;
     constexpr bool FULL = MODE == kModeFull;
     static_assert(!(VARLEN && FULL), "per-row key counts need the bounds checks");
@@ -401,6 +424,8 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
     const int n_waves = blockDim.x >> 6;
     const int Sk = a.Sk;
     const float scale = a.scale;
+    const T* skip_addr = scores;  // what lanes without a valid key read
+    if constexpr (VARLEN) skip_addr = skipped_vector_address<T, VEC>(scores, (long long)a.n_rows * Sk);
 
     int slot = 0;
     for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
@@ -408,7 +433,7 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
         const T* mp = mask_row_ptr<T, MASK>(a, row);
         int klen = Sk;
         if constexpr (VARLEN) {
-            klen = row_key_count(a, row);
+            klen = row_key_count<CAUSAL>(a, row);
             if (klen == 0) continue;  // the whole workgroup skips the row together
         }
 
@@ -419,7 +444,10 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
             int colc = FULL ? (v * (int)blockDim.x + tid) * VEC : vec_start<VEC, UA>((v * (int)blockDim.x + tid) * VEC, Sk);
             if constexpr (VARLEN) {
                 const bool needed = (v * (int)blockDim.x + tid) * VEC < Sk && colc < klen;
-                raw[v] = load_stream<T, VEC, UA>(needed ? rp + colc : scores);
+                if constexpr (CAUSAL)  // as in the wave kernel
+                    raw[v] = load_stream<T, VEC, UA>(rp + (needed ? colc : vec_start<VEC, UA>((klen - 1) / VEC * VEC, Sk)));
+                else
+                    raw[v] = load_stream<T, VEC, UA>(needed ? rp + colc : skip_addr);
             } else {
                 raw[v] = load_stream<T, VEC, UA>(rp + colc);
             }
@@ -486,7 +514,8 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 template <typename T, int VEC, int MK>
 __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxArgs a) {
     constexpr bool MASK = MK == kMaskAdditive;
-    constexpr bool VARLEN = MK == kMaskLengths;
+    constexpr bool VARLEN = mask_by_lengths(MK);
+    constexpr bool CAUSAL = MK == kMaskCausal;
     __shared__ SoftmaxLds lds;
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int tid = threadIdx.x;
@@ -501,7 +530,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
     for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
         int klen = Sk;
         if constexpr (VARLEN) {
-            klen = row_key_count(a, row);
+            klen = row_key_count<CAUSAL>(a, row);
             if (klen == 0) continue;  // the whole workgroup skips the row together
         }
         T* rp = scores + (long long)row * Sk;
@@ -594,40 +623,47 @@ hipError_t launch_softmax_wave(const SoftmaxArgs& a, const LaunchCfg& lc, hipStr
     constexpr int R = rows_in_flight_c(NV, VEC, softmax_wave_target_elems(MK, MODE, NV * VEC));
     constexpr int TILE_ROWS = R * (kWave / G) * kWaveFamilyWaves;
     int n_tiles = (int)(((long long)a.n_rows + TILE_ROWS - 1) / TILE_ROWS);
-    if constexpr (MK == kMaskLengths) {
+    if constexpr (mask_by_lengths(MK)) {
+        // (element-aligned 4-byte rows: see below; with per-request lengths 6 wavefronts per SIMD measured 1-2 % faster
+        // than 7, and 5 faster again by as much for rows of 3 and more vectors per lane)
+        constexpr int WPE = (MODE == kModeUnder && sizeof(T) == 4 && G == 64 && NV >= 2) ? (NV >= 3 ? 5 : 6) : 8;
         if (a.B < kWave && a.q_lengths != nullptr) {
             // live tiles only: at most this many (every request with all its rows), shared by a grid of looping workgroups
             SoftmaxArgs c = a;
             c.compact = 1;
             const long long bound = (long long)a.B * a.H * ((a.Sq + TILE_ROWS - 1) / TILE_ROWS);
             n_tiles = (int)(bound < 0x7FFFFFFF ? bound : 0x7FFFFFFF);
-            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>),
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, WPE>),
                                dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxCompactCap, lc)), dim3(64 * kWaveFamilyWaves), 0, s,
                                c, n_tiles);
             return hipGetLastError();
         }
-    }
-    // Element-aligned 4-byte rows stream best with few wavefronts resident (their accesses straddle cache lines, and the
-    // more of them are in flight the more they thrash): the kernel is built to hold a SIMD at 5 wavefronts (20 per compute
-    // unit), at 4 for rows of 384 floats and more.  Measured on 77..1001 floats, with and without an additive mask:
-    // +1..4 points of HBM peak (config 2: 128.8 -> 123.2 us); 2-byte elements, which have half the bytes in flight per
-    // wavefront, lose with any such limit.  Rows of 384 floats and more have at least 2 vectors per lane on 64 lanes,
-    // shorter rows at most 2, so only that shape needs both builds.
-    const dim3 grid(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)), block(64 * kWaveFamilyWaves);
-    if constexpr (MODE == kModeUnder && sizeof(T) == 4 && MK != kMaskLengths) {
-        if constexpr (G < 64 || NV == 1) {
-            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
-        } else if constexpr (NV >= 3) {
-            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
-        } else if (a.Sk < 384) {
-            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
-        } else {
-            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
-        }
+        hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, WPE>),
+                           dim3(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)), dim3(64 * kWaveFamilyWaves), 0, s, a, n_tiles);
+        return hipGetLastError();
     } else {
-        hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), grid, block, 0, s, a, n_tiles);
+        // Element-aligned 4-byte rows stream best with few wavefronts resident (their accesses straddle cache lines, and the
+        // more of them are in flight the more they thrash): the kernel is built to hold a SIMD at 5 wavefronts (20 per compute
+        // unit), at 4 for rows of 384 floats and more.  Measured on 77..1001 floats, with and without an additive mask:
+        // +1..4 points of HBM peak (config 2: 128.8 -> 123.2 us); 2-byte elements, which have half the bytes in flight per
+        // wavefront, lose with any such limit.  Rows of 384 floats and more have at least 2 vectors per lane on 64 lanes,
+        // shorter rows at most 2, so only that shape needs both builds.
+        const dim3 grid(capped_grid(n_tiles, kWaveFamilyWaves, kSoftmaxWaveCap, lc)), block(64 * kWaveFamilyWaves);
+        if constexpr (MODE == kModeUnder && sizeof(T) == 4) {
+            if constexpr (G < 64 || NV == 1) {
+                hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
+            } else if constexpr (NV >= 3) {
+                hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
+            } else if (a.Sk < 384) {
+                hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 5>), grid, block, 0, s, a, n_tiles);
+            } else {
+                hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE, 4>), grid, block, 0, s, a, n_tiles);
+            }
+        } else {
+            hipLaunchKernelGGL((softmax_wave_kernel<T, VEC, G, NV, MK, MODE>), grid, block, 0, s, a, n_tiles);
+        }
+        return hipGetLastError();
     }
-    return hipGetLastError();
 }
 
 // The shapes the planner can ask for: within the register budget; and with vectors of one or two elements its
@@ -700,7 +736,7 @@ template <typename T, int VEC, int MK, bool UA_OK>
 hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
     switch (row_mode(p)) {
         case kModeFull:
-            if constexpr (MK != kMaskLengths) return launch_softmax_vm<T, VEC, MK, kModeFull>(p, a, lc, s);
+            if constexpr (!mask_by_lengths(MK)) return launch_softmax_vm<T, VEC, MK, kModeFull>(p, a, lc, s);
             break;
         case kModeRagged: return launch_softmax_vm<T, VEC, MK, kModeRagged>(p, a, lc, s);
         case kModeUnder:
@@ -712,7 +748,8 @@ hipError_t launch_softmax_m(const Plan& p, const SoftmaxArgs& a, const LaunchCfg
 
 template <typename T, int VEC, bool UA_OK = false>
 hipError_t launch_softmax_v(const Plan& p, const SoftmaxArgs& a, const LaunchCfg& lc, hipStream_t s) {
-    if (a.k_lengths || a.causal) return launch_softmax_m<T, VEC, kMaskLengths, UA_OK>(p, a, lc, s);
+    if (a.causal) return launch_softmax_m<T, VEC, kMaskCausal, UA_OK>(p, a, lc, s);
+    if (a.k_lengths || a.q_lengths) return launch_softmax_m<T, VEC, kMaskLengths, UA_OK>(p, a, lc, s);
     return a.mask ? launch_softmax_m<T, VEC, kMaskAdditive, UA_OK>(p, a, lc, s)
                   : launch_softmax_m<T, VEC, kMaskNone, UA_OK>(p, a, lc, s);
 }
