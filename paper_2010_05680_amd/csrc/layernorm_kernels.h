@@ -516,11 +516,15 @@ __global__ __launch_bounds__(ROOMY ? 512 : 1024) void layernorm_block_kernel(Lay
     }
 }
 
-// stream family: rows too long for registers; statistics in a first sweep
-// (running Welford state per lane, merged chunk by chunk), output in a second.
+// stream family: rows too long for the block family's registers.  A workgroup of 16 wavefronts owns a row and makes two
+// sweeps over it: statistics first (running Welford state per lane, merged chunk by chunk), output second.  The
+// t = x + bias + residual values of the row's first kStreamLdsElems columns wait in LDS between the sweeps (as binary32,
+// every lane reads back what it wrote itself), so only the columns beyond them are read from memory twice.
+constexpr int kStreamLdsElems = 32768;  // 128 KB of the compute unit's 160 KB: one such workgroup per compute unit
 template <typename T, int VEC, bool RES>
 __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerNormArgs a) {
     __shared__ LayerNormLds lds;
+    __shared__ __attribute__((aligned(16))) float t_lds[kStreamLdsElems];
     const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
     const T* __restrict__ res = reinterpret_cast<const T*>(a.residual);
     const T* __restrict__ bias = reinterpret_cast<const T*>(a.bias);
@@ -532,7 +536,10 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
     const int wave = tid >> 6;
     const int n_waves = blockDim.x >> 6;
     const int hidden = a.hidden;
-    const long long step = (long long)blockDim.x * VEC;
+    const int step = (int)blockDim.x * VEC;
+    constexpr int kStreamUnroll = stream_unroll<VEC>();
+    // columns [0, kept) wait in LDS: the whole row, or a whole number of the workgroup's chunks of `step` columns
+    const int kept = hidden < kStreamLdsElems ? hidden : kStreamLdsElems;
 
     float cnt = 0.f;
     for (long long col = (long long)tid * VEC; col < hidden; col += step) cnt += (float)VEC;
@@ -545,20 +552,11 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
         if (is_padding_row(a, row)) continue;  // uniform over the workgroup
         const long long off = (long long)row * hidden;
         float n_run = 0.f, mu_run = 0.f, q_run = 0.f;
-        for (long long col = (long long)tid * VEC; col < hidden; col += step) {
-            Pack<T, VEC> xr = load_pack<T, VEC>(x + off + col);  // plain: the row is read again below
-            Pack<T, VEC> rr;
-            if constexpr (RES) rr = load_pack<T, VEC>(res + off + col);
-            float b[VEC];
-            load_bias<T, VEC>(bias, (int)col, b);
-            float t[VEC];
+        // one vector of t joins the lane's running statistics
+        auto absorb = [&](const float (&t)[VEC]) {
             float s = 0.f;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                t[j] = (float)xr.v[j] + b[j];
-                if constexpr (RES) t[j] += (float)rr.v[j];
-                s += t[j];
-            }
+            for (int j = 0; j < VEC; ++j) s += t[j];
             const float cm = s * (1.0f / VEC);
             float cq = 0.f;
 #pragma unroll
@@ -569,30 +567,87 @@ __global__ __launch_bounds__(kStreamThreads) void layernorm_stream_kernel(LayerN
             mu_run = fmaf(d, (float)VEC * inv, mu_run);
             q_run = fmaf(d * d, n_run * (float)VEC * inv, q_run + cq);
             n_run = nt;
-        }
+        };
+        // U vectors of the lane, `step` columns apart from `col` on: all loads first, then the arithmetic
+        auto first_sweep = [&](long long col, auto u_tag, auto kept_tag) {
+            constexpr int U = decltype(u_tag)::value;
+            constexpr bool KEPT = decltype(kept_tag)::value;  // all U vectors lie in the kept columns / none does
+            Pack<T, VEC> xr[U], rr[U];
+            float b[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                // kept columns are not read again: streaming loads; the others come back in the second sweep
+                xr[u] = KEPT ? load_stream<T, VEC>(x + off + c) : load_pack<T, VEC>(x + off + c);
+                if constexpr (RES) rr[u] = KEPT ? load_stream<T, VEC>(res + off + c) : load_pack<T, VEC>(res + off + c);
+                load_bias<T, VEC>(bias, (int)c, b[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                float t[VEC];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    t[j] = (float)xr[u].v[j] + b[u][j];
+                    if constexpr (RES) t[j] += (float)rr[u].v[j];
+                }
+                if constexpr (KEPT) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) t_lds[c + j] = t[j];
+                }
+                absorb(t);
+            }
+        };
+        // a lane's columns are tid * VEC + k * step: first those below `kept`, then the rest
+        long long col = (long long)tid * VEC;
+        stream_columns<kStreamUnroll>(col, kept, step, [&](long long c, auto u) { first_sweep(c, u, std::true_type{}); });
+        stream_columns<kStreamUnroll>(col, hidden, step, [&](long long c, auto u) { first_sweep(c, u, std::false_type{}); });
+
         float mean[1] = {mu_run};
         float m2[1] = {q_run};
         merge_stats_step<1, kWave, 0, 1, 6>(mean, m2, w1, w2);
         layernorm_block_combine(lds, slot, wave, lane, n_waves, n_w, mean[0], m2[0]);
         const float rstd = fast_rsqrt(fmaf(m2[0], a.inv_hidden, a.eps));
 
-        for (long long col = (long long)tid * VEC; col < hidden; col += step) {
-            Pack<T, VEC> xr = load_stream<T, VEC>(x + off + col);
-            Pack<T, VEC> rr;
-            if constexpr (RES) rr = load_stream<T, VEC>(res + off + col);
-            float b[VEC], g[VEC], be[VEC];
-            load_bias<T, VEC>(bias, (int)col, b);
-            load_param<T, VEC>(gamma, (int)col, g);
-            load_param<T, VEC>(beta, (int)col, be);
-            Pack<T, VEC> o;
+        auto second_sweep = [&](long long col, auto u_tag, auto kept_tag) {
+            constexpr int U = decltype(u_tag)::value;
+            constexpr bool KEPT = decltype(kept_tag)::value;
+            Pack<T, VEC> xr[U], rr[U];
+            float b[U][VEC], g[U][VEC], be[U][VEC];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                float tv = (float)xr.v[j] + b[j];
-                if constexpr (RES) tv += (float)rr.v[j];
-                o.v[j] = (T)fmaf((tv - mean[0]) * rstd, g[j], be[j]);
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                if constexpr (!KEPT) {
+                    xr[u] = load_stream<T, VEC>(x + off + c);
+                    if constexpr (RES) rr[u] = load_stream<T, VEC>(res + off + c);
+                    load_bias<T, VEC>(bias, (int)c, b[u]);
+                }
+                load_param<T, VEC>(gamma, (int)c, g[u]);
+                load_param<T, VEC>(beta, (int)c, be[u]);
             }
-            store_stream<T, VEC>(out + off + col, o);
-        }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                float t[VEC];
+                if constexpr (KEPT) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) t[j] = t_lds[c + j];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        t[j] = (float)xr[u].v[j] + b[u][j];
+                        if constexpr (RES) t[j] += (float)rr[u].v[j];
+                    }
+                }
+                Pack<T, VEC> o;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) o.v[j] = (T)fmaf((t[j] - mean[0]) * rstd, g[u][j], be[u][j]);
+                store_stream<T, VEC>(out + off + c, o);
+            }
+        };
+        col = (long long)tid * VEC;
+        stream_columns<kStreamUnroll>(col, kept, step, [&](long long c, auto u) { second_sweep(c, u, std::true_type{}); });
+        stream_columns<kStreamUnroll>(col, hidden, step, [&](long long c, auto u) { second_sweep(c, u, std::false_type{}); });
         slot ^= 1;  // only rows that used the LDS slot advance it
     }
 }
@@ -718,8 +773,9 @@ hipError_t launch_layernorm_vr(const Plan& p, const LayerNormArgs& a, const Laun
         }
         return hipErrorInvalidValue;
     }
+    // (its LDS row cache leaves room for one workgroup per compute unit)
     hipLaunchKernelGGL((layernorm_stream_kernel<T, VEC, RES>),
-                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
+                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamThreads / 64, lc)), dim3(kStreamThreads), 0, s, a);
     return hipGetLastError();
 }
 

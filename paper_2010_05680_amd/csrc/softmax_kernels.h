@@ -12,6 +12,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_utils.h"
 #include "plan.h"
 
@@ -64,7 +66,6 @@ constexpr int kSoftmaxWaveCap = 0;
 constexpr int kSoftmaxBlockCap = 0;
 constexpr int kSoftmaxCompactCap = 96;  // length-aware wave family over live tiles only (24 workgroups per compute unit: 16..64 measured alike, 8 was 8 % slower)
 constexpr int kLayerNormBlockCap = 32;  // only with the caller's cap; by default its grid is whole rounds of resident workgroups
-constexpr int kStreamCap = 32;
 
 // Elements of the rows in flight per lane in the wave family: fewer for element-aligned accesses, except with
 // per-request lengths, where half of a lane's vectors are typically not loaded at all.
@@ -508,15 +509,50 @@ __global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
 
 // stream family: rows too long for registers.  First sweep keeps a running
 // (max, sum) per lane, rescaling the sum whenever the maximum grows; after the
-// combine a second sweep re-reads the row and writes the result.  With
+// combine a second sweep writes the result.  The scores of the row's first
+// kStreamLdsBytes wait in LDS between the sweeps (every lane reads back what it
+// wrote itself), so only the columns beyond them are read from memory twice.  With
 // per-request lengths the first sweep stops at the row's last valid key and the
 // second writes zeros beyond it without reading; rows without valid keys are skipped.
+constexpr int kStreamLdsBytes = 128 * 1024;  // of the compute unit's 160 KB: one such workgroup per compute unit
+// LayerNorm: vectors per lane whose loads are issued together (their widened parameters must fit the registers too)
+template <int VEC>
+constexpr int stream_unroll() {
+    return VEC >= 8 ? 2 : VEC == 4 ? 3 : 4;
+}
+
+// Walks a lane's columns col, col + step, ... below `end`: groups of U vectors while they last, then the rest as ONE
+// group of its own size (single vectors would each wait for their own load).  body(first column, group size tag).
+template <int U, typename Body>
+__device__ __forceinline__ void stream_columns(long long& col, long long end, int step, Body body) {
+    for (; col + (long long)(U - 1) * step < end; col += (long long)U * step) body(col, std::integral_constant<int, U>{});
+    if constexpr (U > 3) {
+        if (col + 2ll * step < end) {
+            body(col, std::integral_constant<int, 3>{});
+            col += 3ll * step;
+        }
+    }
+    if constexpr (U > 2) {
+        if (col + (long long)step < end) {
+            body(col, std::integral_constant<int, 2>{});
+            col += 2ll * step;
+        }
+    }
+    if (col < end) {
+        body(col, std::integral_constant<int, 1>{});
+        col += step;
+    }
+}
+
 template <typename T, int VEC, int MK>
 __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxArgs a) {
     constexpr bool MASK = MK == kMaskAdditive;
     constexpr bool VARLEN = mask_by_lengths(MK);
     constexpr bool CAUSAL = MK == kMaskCausal;
+    constexpr int UNROLL = 4;  // vectors per lane whose loads are issued together
+    constexpr int LDS_ELEMS = kStreamLdsBytes / (int)sizeof(T);
     __shared__ SoftmaxLds lds;
+    __shared__ Pack<T, VEC> row_lds[LDS_ELEMS / VEC];
     T* __restrict__ scores = reinterpret_cast<T*>(a.scores);
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -525,6 +561,7 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
     const int Sk = a.Sk;
     const float scale = a.scale;
     const int step = (int)blockDim.x * VEC;
+    using One = std::integral_constant<int, 1>;
 
     int slot = 0;
     for (int row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
@@ -535,33 +572,52 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
         }
         T* rp = scores + (long long)row * Sk;
         const T* mp = mask_row_ptr<T, MASK>(a, row);
+        // columns [0, kept) wait in LDS: every column that is read, or a whole number of the workgroup's chunks
+        const int kept = klen < LDS_ELEMS ? klen : LDS_ELEMS;
 
         // running reference in the exponent domain (see softmax_block_combine): mu_run = fl(max * log2 e)
         float mu_run = -INFINITY, l_run = 0.f;
-        for (long long col = (long long)tid * VEC; col < klen; col += step) {
-            Pack<T, VEC> raw = load_pack<T, VEC>(rp + col);  // plain: the row is read again below
-            Pack<T, VEC> mraw;
-            if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
-            float z[VEC];
-            float cm = -INFINITY;
+        // U vectors of the lane, `step` columns apart from `col` on, all below `kept` or none: loads first, then arithmetic
+        auto first_sweep = [&](long long col, auto u_tag, auto kept_tag) {
+            constexpr int U = decltype(u_tag)::value;
+            constexpr bool KEPT = decltype(kept_tag)::value;
+            Pack<T, VEC> raw[U], mraw[U];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                float s = (float)raw.v[j];
-                if constexpr (MASK)
-                    z[j] = fmaf(s, scale, (float)mraw.v[j]);
-                else
-                    z[j] = s * scale;
-                if constexpr (VARLEN) z[j] = col + j < klen ? z[j] : -INFINITY;  // element 0 of the vector is valid
-                cm = fmaxf(cm, z[j]);
-            }
-            const float cmu = cm * kLog2e;
-            if (cmu > mu_run) {
-                l_run *= fast_exp2(mu_run - cmu);  // first chunk: 0 * exp2(-inf) = 0
-                mu_run = cmu;
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                // kept columns are not read again: streaming loads; the others come back in the second sweep
+                raw[u] = KEPT ? load_stream<T, VEC>(rp + c) : load_pack<T, VEC>(rp + c);
+                if constexpr (MASK) mraw[u] = load_pack<T, VEC>(mp + c);
             }
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) l_run += fast_exp2(fmaf(z[j], kLog2e, -mu_run));
-        }
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                if constexpr (KEPT) row_lds[c / VEC] = raw[u];
+                float z[VEC];
+                float cm = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    float s = (float)raw[u].v[j];
+                    if constexpr (MASK)
+                        z[j] = fmaf(s, scale, (float)mraw[u].v[j]);
+                    else
+                        z[j] = s * scale;
+                    if constexpr (VARLEN) z[j] = c + j < klen ? z[j] : -INFINITY;  // element 0 of the vector is valid
+                    cm = fmaxf(cm, z[j]);
+                }
+                const float cmu = cm * kLog2e;
+                if (cmu > mu_run) {
+                    l_run *= fast_exp2(mu_run - cmu);  // first chunk: 0 * exp2(-inf) = 0
+                    mu_run = cmu;
+                }
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) l_run += fast_exp2(fmaf(z[j], kLog2e, -mu_run));
+            }
+        };
+        // a lane's columns are tid * VEC + k * step: first those below `kept`, then the rest up to the last valid key
+        long long col = (long long)tid * VEC;
+        stream_columns<UNROLL>(col, kept, step, [&](long long c, auto u) { first_sweep(c, u, std::true_type{}); });
+        stream_columns<UNROLL>(col, klen, step, [&](long long c, auto u) { first_sweep(c, u, std::false_type{}); });
 
         float m[1] = {mu_run};
         group_allreduce<kWave, 1>(m, MaxOp{});
@@ -574,29 +630,52 @@ __global__ __launch_bounds__(kStreamThreads) void softmax_stream_kernel(SoftmaxA
         const float f = softmax_block_combine(lds, slot, wave, lane, n_waves, mu_w, l[0]);
         // exp2(z log2 e - mu_w) * f == exp(z - max)/L; a wavefront with no element stores nothing but zeros
         const float shift = (mu_w == -INFINITY) ? 0.f : -mu_w;
-        for (long long col = (long long)tid * VEC; col < Sk; col += step) {
-            Pack<T, VEC> o;
-            if (VARLEN && col >= klen) {
+
+        // SRC: 0 = the vectors wait in LDS, 1 = read them again, 2 = beyond the last valid key (zeros, nothing is read)
+        auto second_sweep = [&](long long col, auto u_tag, auto src_tag) {
+            constexpr int U = decltype(u_tag)::value;
+            constexpr int SRC = decltype(src_tag)::value;
+            Pack<T, VEC> raw[U], mraw[U];
+            if constexpr (SRC != 2) {
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) o.v[j] = (T)0.f;
-            } else {
-                Pack<T, VEC> raw = load_stream<T, VEC>(rp + col);
-                Pack<T, VEC> mraw;
-                if constexpr (MASK) mraw = load_pack<T, VEC>(mp + col);
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    float s = (float)raw.v[j];
-                    float zz;
-                    if constexpr (MASK)
-                        zz = fmaf(s, scale, (float)mraw.v[j]);
-                    else
-                        zz = s * scale;
-                    const float y = fast_exp2(fmaf(zz, kLog2e, shift)) * f;
-                    o.v[j] = (T)((!VARLEN || col + j < klen) ? y : 0.f);
+                for (int u = 0; u < U; ++u) {
+                    const long long c = col + (long long)u * step;
+                    if constexpr (SRC == 1) raw[u] = load_stream<T, VEC>(rp + c);
+                    if constexpr (MASK) mraw[u] = load_pack<T, VEC>(mp + c);
                 }
             }
-            store_stream<T, VEC>(rp + col, o);
-        }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long c = col + (long long)u * step;
+                Pack<T, VEC> o;
+                if constexpr (SRC == 2) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o.v[j] = (T)0.f;
+                } else {
+                    if constexpr (SRC == 0) raw[u] = row_lds[c / VEC];
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        float s = (float)raw[u].v[j];
+                        float zz;
+                        if constexpr (MASK)
+                            zz = fmaf(s, scale, (float)mraw[u].v[j]);
+                        else
+                            zz = s * scale;
+                        const float y = fast_exp2(fmaf(zz, kLog2e, shift)) * f;
+                        o.v[j] = (T)((!VARLEN || c + j < klen) ? y : 0.f);
+                    }
+                }
+                store_stream<T, VEC>(rp + c, o);
+            }
+        };
+        using Lds = std::integral_constant<int, 0>;
+        using Again = std::integral_constant<int, 1>;
+        using Zeros = std::integral_constant<int, 2>;
+        col = (long long)tid * VEC;
+        stream_columns<UNROLL>(col, kept, step, [&](long long c, auto u) { second_sweep(c, u, Lds{}); });
+        stream_columns<UNROLL>(col, klen, step, [&](long long c, auto u) { second_sweep(c, u, Again{}); });
+        if constexpr (VARLEN)
+            for (; col < Sk; col += step) second_sweep(col, One{}, Zeros{});
         slot ^= 1;  // only rows that used the LDS slot advance it (skipped rows execute no barrier)
     }
 }
@@ -726,8 +805,9 @@ hipError_t launch_softmax_vm(const Plan& p, const SoftmaxArgs& a, const LaunchCf
         }
         return hipErrorInvalidValue;
     }
+    // (its LDS row cache leaves room for one workgroup per compute unit)
     hipLaunchKernelGGL((softmax_stream_kernel<T, VEC, MK>),
-                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamCap, lc)), dim3(kStreamThreads), 0, s, a);
+                       dim3(capped_grid(a.n_rows, kStreamThreads / 64, kStreamThreads / 64, lc)), dim3(kStreamThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -198,6 +198,31 @@ def test_long_rows_block_and_stream_families():
     assert_parity(_np(gu.run_layernorm(case)), gu.oracle_layernorm(case), F16, "layernorm f16 hidden=40000")
 
 
+@pytest.mark.parametrize("dtype", [F32, F16])
+def test_rows_around_the_lds_row_cache_of_the_stream_family(dtype):
+    """The stream family parks the first 128 KB of a row in LDS between its two sweeps and reads the rest twice.
+    Row lengths on both sides of that boundary, with every size of leftover group of vectors in both parts."""
+    es = np.dtype(dtype).itemsize
+    vec = 16 // es
+    cached = (128 * 1024) // es           # softmax: columns that wait in LDS
+    chunk = 1024 * vec                    # columns one pass of the workgroup covers
+    lengths = [cached + vec, cached + chunk + vec, cached + 2 * chunk + 3 * vec, cached + 3 * chunk, cached + 4 * chunk + vec,
+               cached - chunk + vec, cached + 1, cached + 7 * vec + 2]
+    for n, Sk in enumerate(lengths):
+        for mask_kind in ("none", "key"):
+            case = wl.random_softmax_case(1200 + n, 1, 1, 2, Sk, dtype=dtype, mask_kind=mask_kind, score_std=4.0)
+            with gu.overrides(path=tb.PATH_STREAM):
+                got = _np(gu.run_softmax(case))
+            assert_parity(got, gu.oracle_softmax(case), dtype, f"softmax {np.dtype(dtype).name} Sk={Sk} mask={mask_kind}")
+    ln_cached = 32768                     # LayerNorm: columns of t (binary32) that wait in LDS
+    for n, hidden in enumerate([ln_cached + vec, ln_cached + chunk + vec, ln_cached + 2 * chunk + 3 * vec, ln_cached + 3 * chunk,
+                                ln_cached - chunk + vec, ln_cached + 1, 3 * ln_cached + 5 * vec]):
+        case = wl.random_layernorm_case(1300 + n, 3, hidden, dtype=dtype, eps=1e-5)
+        with gu.overrides(path=tb.PATH_STREAM):
+            got = _np(gu.run_layernorm(case))
+        assert_parity(got, gu.oracle_layernorm(case), dtype, f"layernorm {np.dtype(dtype).name} hidden={hidden}")
+
+
 def test_small_grid_makes_workgroups_loop_over_tiles():
     with gu.overrides(grid_waves=1):
         case = wl.softmax_case(wl.config_spec(1))
