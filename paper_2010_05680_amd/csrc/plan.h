@@ -8,7 +8,8 @@
 //            registers; a wavefront works on R * (64/G) rows at once.
 //   block  : a workgroup of W wavefronts owns a row; per-wavefront partial
 //            results are combined through LDS with one barrier.
-//   stream : a workgroup owns a row too long for registers and reads it twice.
+//   stream : a workgroup owns a row too long for registers and makes two sweeps over it; the row's first
+//            128 KB wait in LDS in between, the rest is read twice.
 #pragma once
 #include <cstdio>
 
