@@ -409,8 +409,18 @@ __device__ __forceinline__ float softmax_block_combine(SoftmaxLds& lds, int slot
 }
 
 // block family: a workgroup of blockDim.x/64 wavefronts per row, NV vectors per lane.
+// Wavefronts per SIMD the kernel is built to allow at least: 4 lets one workgroup of 16 wavefronts onto a compute unit (what
+// 1024 threads need anyway); 8 makes the compiler stay within 64 registers so that two fit, for the one shape that would
+// otherwise miss it by two registers (32768 halfs per row: 4 vectors of 8 per lane).
 template <typename T, int VEC, int NV, int MK, int MODE>
-__global__ __launch_bounds__(1024) void softmax_block_kernel(SoftmaxArgs a) {
+constexpr int softmax_block_min_waves() {
+    // (with an additive mask on element-aligned rows the shape does not fit 64 registers)
+    return (sizeof(T) == 2 && VEC == 8 && NV == 4 && !mask_by_lengths(MK) && !(MK == kMaskAdditive && MODE == kModeUnder)) ? 8 : 4;
+}
+
+template <typename T, int VEC, int NV, int MK, int MODE>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(softmax_block_min_waves<T, VEC, NV, MK, MODE>(), 8)))
+void softmax_block_kernel(SoftmaxArgs a) {
     constexpr bool MASK = MK == kMaskAdditive;
     constexpr bool VARLEN = mask_by_lengths(MK);
     constexpr bool CAUSAL = MK == kMaskCausal;
